@@ -1,0 +1,565 @@
+/*
+ * climber_oracle.c -- fp64 CPU oracle for the Climber serving hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing in the product library may include, link
+ * or call this file; it shares no code, header, table or helper with the HIP
+ * path.  Only the test-suite, the smoke check and the benchmark's cpu_baseline
+ * leg use it.
+ *
+ * Everything here is the plain definition written out as direct loops in
+ * double precision: every softmax row is materialised in full, there is no
+ * tiling, no online softmax, no cache reuse trick and no re-ordering beyond
+ * what the definition states.
+ *
+ * What it follows (Climber, arXiv 2502.09888):
+ *   - Adaptive Transformer Layer, Sec. 3.1.3, Eq. (3):
+ *       R = Q K^T (+ bias, taken as 0 here), A = Softmax(R / f_tc), out = A V
+ *     The equation carries no 1/sqrt(d_k); a caller-supplied qk_scale
+ *     multiplies Q K^T so that both readings can be expressed.
+ *   - the temperature f_tc is a positive scalar chosen per query row from a
+ *     table indexed by (scenario, behaviour) (Sec. 3.1.3, text after Eq. (3)).
+ *   - Multi-scale sequence extraction, Sec. 3.1.2: the history is split into
+ *     equal subsequences, each handled by its own attention => history tokens
+ *     only see tokens of their own subsequence (block-diagonal attention).
+ *   - "single user, multiple items" mask, Sec. 3.2: a candidate sees the whole
+ *     history and itself, never another candidate.
+ *   - serving flow, Sec. 3.2: per-layer history K/V are computed once and the
+ *     candidates attend to them.
+ *   - layer composition (pre-RMSNorm, output projection, residuals, erf-GELU
+ *     feed-forward, no bias vectors) is not given by the paper; it is the
+ *     convention this build fixes for f_QKV / f_FFN of Eq. (3).
+ *
+ * Layouts: every activation is token-major, [tokens][H][d_head] for q/k/v and
+ * [tokens][H*d_head] for attention outputs.  Histories of a batch are packed
+ * with per-user padded offsets tok_off[B+1]; user b owns rows
+ * tok_off[b] .. tok_off[b+1]-1 of which the first hist_len[b] are valid.
+ * Candidates are packed with offsets cand_off[B+1].
+ *
+ * Return value: 0 on success, negative on invalid input (id outside the
+ * table, temperature not finite or <= 0, a query row with no visible key).
+ *
+ * Parity pins (see tests): library softmax attention at tau = 1, row-scaled
+ * library attention for general tau, closed forms (tau -> inf mean, tau -> 0
+ * arg-max, two-key hand formula), convexity, brute force of a candidate
+ * appended alone to the history, numpy one-liners for the layer pieces.
+ * Model *quality* numbers of the paper (AUC tables) need its data and weights
+ * and are not pinned: parity unpinned for those.
+ */
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ID (-1)
+#define ORACLE_ERR_TAU (-2)
+#define ORACLE_ERR_EMPTY_ROW (-3)
+#define ORACLE_ERR_ALLOC (-4)
+
+/* ---- temperature table lookup: tau_i = T[scen_i][beh_i] ------------------ */
+static int lookup_tau(const double *tau, int n_scen, int n_beh, int scen, int beh, double *out)
+{
+    if (scen < 0 || scen >= n_scen || beh < 0 || beh >= n_beh)
+        return ORACLE_ERR_ID;
+    double t = tau[(size_t)scen * n_beh + beh];
+    if (!(t > 0.0) || isinf(t) || isnan(t))
+        return ORACLE_ERR_TAU;
+    *out = t;
+    return ORACLE_OK;
+}
+
+/*
+ * One softmax-attention row over an explicit list of visible keys.
+ *   logits r_j = qk_scale * <q, k_j>, a = softmax_j(r_j / tau), o = sum a_j v_j
+ * keys/vals are given as arrays of row pointers so that the caller decides
+ * what is visible.  a_out (nullable) receives the n_vis probabilities.
+ */
+static void attention_row(int dh, const double *q, int n_vis, const double *const *keys,
+                          const double *const *vals, double tau, double qk_scale,
+                          double *scratch /* n_vis */, double *o /* dh */, double *a_out)
+{
+    double mx = -INFINITY;
+    for (int j = 0; j < n_vis; ++j) {
+        double dot = 0.0;
+        for (int e = 0; e < dh; ++e)
+            dot += q[e] * keys[j][e];
+        scratch[j] = (qk_scale * dot) / tau;
+        if (scratch[j] > mx)
+            mx = scratch[j];
+    }
+    double sum = 0.0;
+    for (int j = 0; j < n_vis; ++j) {
+        scratch[j] = exp(scratch[j] - mx);
+        sum += scratch[j];
+    }
+    for (int e = 0; e < dh; ++e)
+        o[e] = 0.0;
+    for (int j = 0; j < n_vis; ++j) {
+        double a = scratch[j] / sum;
+        if (a_out)
+            a_out[j] = a;
+        for (int e = 0; e < dh; ++e)
+            o[e] += a * vals[j][e];
+    }
+}
+
+/* ---- the general definition with an explicit visibility matrix ----------- */
+/*
+ * q,k,v: [n][H][dh]; tau_row: [n]; visible: [n][n] (row i sees column j iff
+ * non-zero); o: [n][H*dh]; a (nullable): [H][n][n] with zeros where masked.
+ */
+int oracle_masked_attention(int n, int H, int dh, const double *q, const double *k,
+                            const double *v, const double *tau_row, const uint8_t *visible,
+                            double qk_scale, double *o, double *a)
+{
+    int rc = ORACLE_OK;
+    const size_t row = (size_t)H * dh;
+    for (int i = 0; i < n; ++i)
+        if (!(tau_row[i] > 0.0) || isinf(tau_row[i]))
+            return ORACLE_ERR_TAU;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int h = 0; h < H; ++h) {
+        for (int i = 0; i < n; ++i) {
+            const double **keys = malloc(sizeof(*keys) * (size_t)n);
+            const double **vals = malloc(sizeof(*vals) * (size_t)n);
+            int *idx = malloc(sizeof(int) * (size_t)n);
+            double *s = malloc(sizeof(double) * (size_t)n);
+            double *p = malloc(sizeof(double) * (size_t)n);
+            if (!keys || !vals || !idx || !s || !p) {
+#pragma omp atomic write
+                rc = ORACLE_ERR_ALLOC;
+            } else {
+                int nv = 0;
+                for (int j = 0; j < n; ++j)
+                    if (visible[(size_t)i * n + j]) {
+                        keys[nv] = k + (size_t)j * row + (size_t)h * dh;
+                        vals[nv] = v + (size_t)j * row + (size_t)h * dh;
+                        idx[nv++] = j;
+                    }
+                if (nv == 0) {
+#pragma omp atomic write
+                    rc = ORACLE_ERR_EMPTY_ROW;
+                } else {
+                    attention_row(dh, q + (size_t)i * row + (size_t)h * dh, nv, keys, vals,
+                                  tau_row[i], qk_scale, s, o + (size_t)i * row + (size_t)h * dh, p);
+                    if (a) {
+                        double *arow = a + ((size_t)h * n + i) * n;
+                        for (int j = 0; j < n; ++j)
+                            arow[j] = 0.0;
+                        for (int t = 0; t < nv; ++t)
+                            arow[idx[t]] = p[t];
+                    }
+                }
+            }
+            free(keys); free(vals); free(idx); free(s); free(p);
+        }
+    }
+    return rc;
+}
+
+/* ---- history attention: block-diagonal over equal subsequences ----------- */
+/*
+ * History token i of user b (i < hist_len[b]) lies in subsequence i / sub_len
+ * (sub_len <= 0: a single subsequence) and sees exactly the valid tokens of
+ * that subsequence (and only j <= i when causal != 0).
+ * q,k,v: [T_pad][H][dh]; scen,beh: [T_pad]; tau: [n_scen][n_beh];
+ * o: [T_pad][H*dh], rows of padding are set to 0.
+ */
+int oracle_attn_history(int B, const int32_t *tok_off, const int32_t *hist_len, int H, int dh,
+                        int sub_len, int causal, const double *q, const double *k,
+                        const double *v, const int32_t *scen, const int32_t *beh,
+                        const double *tau, int n_scen, int n_beh, double qk_scale, double *o)
+{
+    int rc = ORACLE_OK;
+    const size_t row = (size_t)H * dh;
+    for (int b = 0; b < B; ++b) {
+        int Lp = tok_off[b + 1] - tok_off[b];
+        if (hist_len[b] < 0 || hist_len[b] > Lp)
+            return ORACLE_ERR_ID;
+        for (int i = hist_len[b]; i < Lp; ++i)
+            memset(o + (size_t)(tok_off[b] + i) * row, 0, sizeof(double) * row);
+    }
+    for (int b = 0; b < B; ++b) {
+        const int Lb = hist_len[b];
+        const size_t base = (size_t)tok_off[b];
+#pragma omp parallel for collapse(2) schedule(dynamic, 8)
+        for (int h = 0; h < H; ++h) {
+            for (int i = 0; i < Lb; ++i) {
+                double t;
+                int e = lookup_tau(tau, n_scen, n_beh, scen[base + i], beh[base + i], &t);
+                if (e) {
+#pragma omp atomic write
+                    rc = e;
+                    continue;
+                }
+                int lo = 0, hi = Lb;
+                if (sub_len > 0) {
+                    lo = (i / sub_len) * sub_len;
+                    hi = lo + sub_len < Lb ? lo + sub_len : Lb;
+                }
+                if (causal)
+                    hi = i + 1;
+                int nv = hi - lo;
+                const double **keys = malloc(sizeof(*keys) * (size_t)nv);
+                const double **vals = malloc(sizeof(*vals) * (size_t)nv);
+                double *s = malloc(sizeof(double) * (size_t)nv);
+                if (!keys || !vals || !s) {
+#pragma omp atomic write
+                    rc = ORACLE_ERR_ALLOC;
+                } else {
+                    for (int j = lo; j < hi; ++j) {
+                        keys[j - lo] = k + (base + j) * row + (size_t)h * dh;
+                        vals[j - lo] = v + (base + j) * row + (size_t)h * dh;
+                    }
+                    attention_row(dh, q + (base + i) * row + (size_t)h * dh, nv, keys, vals, t,
+                                  qk_scale, s, o + (base + i) * row + (size_t)h * dh, NULL);
+                }
+                free(keys); free(vals); free(s);
+            }
+        }
+    }
+    return rc;
+}
+
+/* ---- SUMI attention: candidates against the history K/V plus themselves -- */
+/*
+ * Candidate c of user b sees the hist_len[b] valid history keys of that user
+ * (all subsequences) and its own key/value; nothing else.
+ * kh,vh: [T_pad][H][dh] history; qc,kc,vc: [M_tot][H][dh]; cscen,cbeh: [M_tot];
+ * oc: [M_tot][H*dh].
+ */
+int oracle_attn_sumi(int B, const int32_t *tok_off, const int32_t *hist_len,
+                     const int32_t *cand_off, int H, int dh, const double *kh, const double *vh,
+                     const double *qc, const double *kc, const double *vc, const int32_t *cscen,
+                     const int32_t *cbeh, const double *tau, int n_scen, int n_beh,
+                     double qk_scale, double *oc)
+{
+    int rc = ORACLE_OK;
+    const size_t row = (size_t)H * dh;
+    for (int b = 0; b < B; ++b) {
+        const int Lb = hist_len[b];
+        const size_t base = (size_t)tok_off[b];
+        const int c0 = cand_off[b], c1 = cand_off[b + 1];
+#pragma omp parallel for collapse(2) schedule(dynamic, 8)
+        for (int h = 0; h < H; ++h) {
+            for (int c = c0; c < c1; ++c) {
+                double t;
+                int e = lookup_tau(tau, n_scen, n_beh, cscen[c], cbeh[c], &t);
+                if (e) {
+#pragma omp atomic write
+                    rc = e;
+                    continue;
+                }
+                int nv = Lb + 1;
+                const double **keys = malloc(sizeof(*keys) * (size_t)nv);
+                const double **vals = malloc(sizeof(*vals) * (size_t)nv);
+                double *s = malloc(sizeof(double) * (size_t)nv);
+                if (!keys || !vals || !s) {
+#pragma omp atomic write
+                    rc = ORACLE_ERR_ALLOC;
+                } else {
+                    for (int j = 0; j < Lb; ++j) {
+                        keys[j] = kh + (base + j) * row + (size_t)h * dh;
+                        vals[j] = vh + (base + j) * row + (size_t)h * dh;
+                    }
+                    keys[Lb] = kc + (size_t)c * row + (size_t)h * dh;
+                    vals[Lb] = vc + (size_t)c * row + (size_t)h * dh;
+                    attention_row(dh, qc + (size_t)c * row + (size_t)h * dh, nv, keys, vals, t,
+                                  qk_scale, s, oc + (size_t)c * row + (size_t)h * dh, NULL);
+                }
+                free(keys); free(vals); free(s);
+            }
+        }
+    }
+    return rc;
+}
+
+/* ---- layer pieces --------------------------------------------------------- */
+
+/* y_i = x_i / sqrt(mean_e x_ie^2 + eps) * g   (row-wise RMSNorm with gain) */
+void oracle_rmsnorm(int n, int d, const double *x, const double *g, double eps, double *y)
+{
+#pragma omp parallel for
+    for (int i = 0; i < n; ++i) {
+        double ss = 0.0;
+        for (int e = 0; e < d; ++e)
+            ss += x[(size_t)i * d + e] * x[(size_t)i * d + e];
+        double r = 1.0 / sqrt(ss / d + eps);
+        for (int e = 0; e < d; ++e)
+            y[(size_t)i * d + e] = x[(size_t)i * d + e] * r * g[e];
+    }
+}
+
+/* y = x W, x: [n][din], W: [din][dout] row-major, y: [n][dout] */
+void oracle_linear(int n, int din, int dout, const double *x, const double *W, double *y)
+{
+#pragma omp parallel for
+    for (int i = 0; i < n; ++i) {
+        double *yi = y + (size_t)i * dout;
+        for (int j = 0; j < dout; ++j)
+            yi[j] = 0.0;
+        for (int e = 0; e < din; ++e) {
+            double xe = x[(size_t)i * din + e];
+            const double *We = W + (size_t)e * dout;
+            for (int j = 0; j < dout; ++j)
+                yi[j] += xe * We[j];
+        }
+    }
+}
+
+/* exact GELU: 0.5 x (1 + erf(x / sqrt 2)) */
+void oracle_gelu(size_t n, const double *x, double *y)
+{
+#pragma omp parallel for
+    for (size_t i = 0; i < n; ++i)
+        y[i] = 0.5 * x[i] * (1.0 + erf(x[i] / sqrt(2.0)));
+}
+
+typedef struct {
+    int n_layers, d_model, n_heads, d_head, d_ffn;
+    int n_scen, n_beh;
+    int sub_len; /* <= 0: one subsequence */
+    int causal;
+    double qk_scale, rms_eps;
+} oracle_cfg;
+
+typedef struct { /* one layer, all row-major fp64 */
+    const double *g1;   /* [d] */
+    const double *Wqkv; /* [d][3d]  columns: Q heads | K heads | V heads */
+    const double *Wo;   /* [d][d] */
+    const double *g2;   /* [d] */
+    const double *W1;   /* [d][F] */
+    const double *W2;   /* [F][d] */
+} oracle_layer_w;
+
+/* split [n][3d] projections into three [n][d] arrays */
+static void split_qkv(int n, int d, const double *qkv, double *q, double *k, double *v)
+{
+    for (int i = 0; i < n; ++i) {
+        memcpy(q + (size_t)i * d, qkv + (size_t)i * 3 * d, sizeof(double) * d);
+        memcpy(k + (size_t)i * d, qkv + (size_t)i * 3 * d + d, sizeof(double) * d);
+        memcpy(v + (size_t)i * d, qkv + (size_t)i * 3 * d + 2 * d, sizeof(double) * d);
+    }
+}
+
+/* h = x + o Wo ;  y = h + GELU(RMSNorm(h; g2) W1) W2      (x, o, y: [n][d]) */
+static int post_attention(const oracle_cfg *c, const oracle_layer_w *w, int n, const double *x,
+                          const double *o, double *y)
+{
+    const int d = c->d_model, F = c->d_ffn;
+    double *h = malloc(sizeof(double) * (size_t)n * d);
+    double *hn = malloc(sizeof(double) * (size_t)n * d);
+    double *u = malloc(sizeof(double) * (size_t)n * F);
+    int rc = ORACLE_OK;
+    if (!h || !hn || !u) {
+        rc = ORACLE_ERR_ALLOC;
+    } else {
+        oracle_linear(n, d, d, o, w->Wo, h);
+        for (size_t t = 0; t < (size_t)n * d; ++t)
+            h[t] += x[t];
+        oracle_rmsnorm(n, d, h, w->g2, c->rms_eps, hn);
+        oracle_linear(n, d, F, hn, w->W1, u);
+        oracle_gelu((size_t)n * F, u, u);
+        oracle_linear(n, F, d, u, w->W2, y);
+        for (size_t t = 0; t < (size_t)n * d; ++t)
+            y[t] += h[t];
+    }
+    free(h); free(hn); free(u);
+    return rc;
+}
+
+/* RMSNorm(x; g1) Wqkv -> q, k, v  (each [n][d]) */
+static int project_qkv(const oracle_cfg *c, const oracle_layer_w *w, int n, const double *x,
+                       double *q, double *k, double *v)
+{
+    const int d = c->d_model;
+    double *xn = malloc(sizeof(double) * (size_t)n * d);
+    double *qkv = malloc(sizeof(double) * (size_t)n * 3 * d);
+    int rc = ORACLE_OK;
+    if (!xn || !qkv) {
+        rc = ORACLE_ERR_ALLOC;
+    } else {
+        oracle_rmsnorm(n, d, x, w->g1, c->rms_eps, xn);
+        oracle_linear(n, d, 3 * d, xn, w->Wqkv, qkv);
+        split_qkv(n, d, qkv, q, k, v);
+    }
+    free(xn); free(qkv);
+    return rc;
+}
+
+/*
+ * One layer over an arbitrary sequence with an explicit visibility matrix:
+ * the form the brute force uses.  x,y: [n][d]; tau_row: [n]; visible [n][n];
+ * k_out, v_out (nullable): [n][d] the layer's keys / values.
+ */
+int oracle_layer_masked(const oracle_cfg *c, const oracle_layer_w *w, int n, const double *x,
+                        const double *tau_row, const uint8_t *visible, double *y, double *k_out,
+                        double *v_out)
+{
+    const int d = c->d_model;
+    if (c->n_heads * c->d_head != d)
+        return ORACLE_ERR_ID;
+    double *q = malloc(sizeof(double) * (size_t)n * d);
+    double *k = malloc(sizeof(double) * (size_t)n * d);
+    double *v = malloc(sizeof(double) * (size_t)n * d);
+    double *o = malloc(sizeof(double) * (size_t)n * d);
+    int rc = ORACLE_OK;
+    if (!q || !k || !v || !o)
+        rc = ORACLE_ERR_ALLOC;
+    if (!rc)
+        rc = project_qkv(c, w, n, x, q, k, v);
+    if (!rc)
+        rc = oracle_masked_attention(n, c->n_heads, c->d_head, q, k, v, tau_row, visible,
+                                     c->qk_scale, o, NULL);
+    if (!rc)
+        rc = post_attention(c, w, n, x, o, y);
+    if (!rc && k_out)
+        memcpy(k_out, k, sizeof(double) * (size_t)n * d);
+    if (!rc && v_out)
+        memcpy(v_out, v, sizeof(double) * (size_t)n * d);
+    free(q); free(k); free(v); free(o);
+    return rc;
+}
+
+/*
+ * Brute force for one user and ONE candidate ("single user, single item"):
+ * the candidate is appended alone to the valid history, the whole sequence of
+ * L+1 rows runs through every layer from scratch with the visibility rule
+ * (history rows: own subsequence; last row: everything), and the last row of
+ * the final layer is the candidate's result.   x_hist: [L][d] valid rows only.
+ * tau: [n_layers][n_scen][n_beh].
+ */
+int oracle_stack_bruteforce(const oracle_cfg *c, const oracle_layer_w *w, const double *tau, int L,
+                            const double *x_hist, const int32_t *scen, const int32_t *beh,
+                            const double *x_cand, int cscen, int cbeh, double *y_cand)
+{
+    const int d = c->d_model, n = L + 1;
+    double *x = malloc(sizeof(double) * (size_t)n * d);
+    double *y = malloc(sizeof(double) * (size_t)n * d);
+    double *trow = malloc(sizeof(double) * (size_t)n);
+    uint8_t *vis = calloc((size_t)n * n, 1);
+    int rc = ORACLE_OK;
+    if (!x || !y || !trow || !vis) {
+        rc = ORACLE_ERR_ALLOC;
+    } else {
+        memcpy(x, x_hist, sizeof(double) * (size_t)L * d);
+        memcpy(x + (size_t)L * d, x_cand, sizeof(double) * d);
+        for (int i = 0; i < L; ++i)
+            for (int j = 0; j < L; ++j) {
+                int same = c->sub_len > 0 ? (i / c->sub_len == j / c->sub_len) : 1;
+                vis[(size_t)i * n + j] = (uint8_t)(same && (!c->causal || j <= i));
+            }
+        for (int j = 0; j < n; ++j)
+            vis[(size_t)L * n + j] = 1;
+        for (int l = 0; l < c->n_layers && !rc; ++l) {
+            const double *tl = tau + (size_t)l * c->n_scen * c->n_beh;
+            for (int i = 0; i < n && !rc; ++i)
+                rc = lookup_tau(tl, c->n_scen, c->n_beh, i < L ? scen[i] : cscen,
+                                i < L ? beh[i] : cbeh, &trow[i]);
+            if (!rc)
+                rc = oracle_layer_masked(c, &w[l], n, x, trow, vis, y, NULL, NULL);
+            double *tmp = x; x = y; y = tmp;
+        }
+        if (!rc)
+            memcpy(y_cand, x + (size_t)L * d, sizeof(double) * d);
+    }
+    free(x); free(y); free(trow); free(vis);
+    return rc;
+}
+
+/*
+ * History encode (serving flow, first phase): run the packed histories through
+ * all layers with block-diagonal attention and keep each layer's K and V.
+ * x_hist: [T_pad][d]; k_cache, v_cache: [n_layers][T_pad][d];
+ * y_hist (nullable): [T_pad][d] final-layer history states.
+ * Padding rows are carried along but never visible; their values are
+ * meaningless (they are computed from whatever x_hist holds there, which must
+ * be finite).
+ */
+int oracle_stack_encode(const oracle_cfg *c, const oracle_layer_w *w, const double *tau, int B,
+                        const int32_t *tok_off, const int32_t *hist_len, const double *x_hist,
+                        const int32_t *scen, const int32_t *beh, double *k_cache, double *v_cache,
+                        double *y_hist)
+{
+    const int d = c->d_model, n = tok_off[B];
+    double *x = malloc(sizeof(double) * (size_t)n * d);
+    double *y = malloc(sizeof(double) * (size_t)n * d);
+    double *q = malloc(sizeof(double) * (size_t)n * d);
+    double *o = malloc(sizeof(double) * (size_t)n * d);
+    int rc = ORACLE_OK;
+    if (!x || !y || !q || !o)
+        rc = ORACLE_ERR_ALLOC;
+    else
+        memcpy(x, x_hist, sizeof(double) * (size_t)n * d);
+    for (int l = 0; l < c->n_layers && !rc; ++l) {
+        double *k = k_cache + (size_t)l * n * d, *v = v_cache + (size_t)l * n * d;
+        rc = project_qkv(c, &w[l], n, x, q, k, v);
+        if (!rc)
+            rc = oracle_attn_history(B, tok_off, hist_len, c->n_heads, c->d_head, c->sub_len,
+                                     c->causal, q, k, v, scen, beh,
+                                     tau + (size_t)l * c->n_scen * c->n_beh, c->n_scen, c->n_beh,
+                                     c->qk_scale, o);
+        if (!rc)
+            rc = post_attention(c, &w[l], n, x, o, y);
+        double *tmp = x; x = y; y = tmp;
+    }
+    if (!rc && y_hist)
+        memcpy(y_hist, x, sizeof(double) * (size_t)n * d);
+    free(x); free(y); free(q); free(o);
+    return rc;
+}
+
+/*
+ * Candidate scoring (serving flow, second phase): the packed candidates run
+ * through all layers; in layer l they attend to the cached history K/V of
+ * layer l plus themselves.   x_cand, y_cand: [M_tot][d].
+ */
+int oracle_stack_score(const oracle_cfg *c, const oracle_layer_w *w, const double *tau, int B,
+                       const int32_t *tok_off, const int32_t *hist_len, const double *k_cache,
+                       const double *v_cache, const int32_t *cand_off, const double *x_cand,
+                       const int32_t *cscen, const int32_t *cbeh, double *y_cand)
+{
+    const int d = c->d_model, n = tok_off[B], m = cand_off[B];
+    double *x = malloc(sizeof(double) * (size_t)m * d);
+    double *y = malloc(sizeof(double) * (size_t)m * d);
+    double *q = malloc(sizeof(double) * (size_t)m * d);
+    double *k = malloc(sizeof(double) * (size_t)m * d);
+    double *v = malloc(sizeof(double) * (size_t)m * d);
+    double *o = malloc(sizeof(double) * (size_t)m * d);
+    int rc = ORACLE_OK;
+    if (!x || !y || !q || !k || !v || !o)
+        rc = ORACLE_ERR_ALLOC;
+    else
+        memcpy(x, x_cand, sizeof(double) * (size_t)m * d);
+    for (int l = 0; l < c->n_layers && !rc; ++l) {
+        rc = project_qkv(c, &w[l], m, x, q, k, v);
+        if (!rc)
+            rc = oracle_attn_sumi(B, tok_off, hist_len, cand_off, c->n_heads, c->d_head,
+                                  k_cache + (size_t)l * n * d, v_cache + (size_t)l * n * d, q, k,
+                                  v, cscen, cbeh, tau + (size_t)l * c->n_scen * c->n_beh,
+                                  c->n_scen, c->n_beh, c->qk_scale, o);
+        if (!rc)
+            rc = post_attention(c, &w[l], m, x, o, y);
+        double *tmp = x; x = y; y = tmp;
+    }
+    if (!rc)
+        memcpy(y_cand, x, sizeof(double) * (size_t)m * d);
+    free(x); free(y); free(q); free(k); free(v); free(o);
+    return rc;
+}
+
+int oracle_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp single
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}
