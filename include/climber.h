@@ -1,0 +1,210 @@
+/*
+ * climber.h -- C ABI of the MI355X-native Climber serving hot path.
+ *
+ * The library implements the serving flow of Climber (arXiv 2502.09888, Sec. 3.2
+ * "Deployment"): a user's behaviour history is encoded once, its per-layer keys
+ * and values are kept in a cache in device memory, and M candidate items are then
+ * scored in one batch ("single user, multiple items"): every candidate attends to
+ * the whole cached history plus itself and never to another candidate.  The
+ * attention is the Adaptive Transformer Layer of Sec. 3.1.3, Eq. (3): logits
+ * R = qk_scale * Q K^T are divided by a temperature looked up per query row from a
+ * (scenario, behaviour) table before the softmax.  History tokens only attend
+ * inside their own subsequence (multi-scale sequence extraction, Sec. 3.1.2), i.e.
+ * block-diagonal attention over equal subsequences of `sub_len` tokens.
+ *
+ * General rules
+ *  - Every function returns 0 (CLIMBER_OK) or a negative CLIMBER_ERR_* code;
+ *    climber_strerror() names it.  No exceptions, no output on stderr.
+ *  - "dev" pointers are device (HBM) addresses owned by the caller; the library
+ *    never allocates, frees or keeps them beyond what is documented for the KV
+ *    cache handle.  "host" pointers are ordinary host memory, read during the call.
+ *  - All device work is enqueued on the caller's stream (`stream` is a hipStream_t
+ *    passed as void*; NULL is the default stream).  Compute calls do not
+ *    synchronise; they return after the launches are enqueued.
+ *  - Arguments are validated on the host before anything is launched; a failed
+ *    call has launched nothing.  Device-resident ids cannot be checked on the
+ *    host: scenario / behaviour ids outside the table are clamped into range by
+ *    the kernels (results for such rows are then those of the clamped id).
+ *    Temperatures must be finite and > 0; this is the caller's contract (a
+ *    non-positive entry gives unspecified values for the rows that use it, never
+ *    an out-of-bounds access).
+ *  - Packed batches: the histories of the B users of a batch are stored back to
+ *    back with per-user padded lengths; user b owns rows
+ *    tok_off[b] .. tok_off[b] + hist_len_padded[b] - 1 of every per-token array,
+ *    of which the first hist_len[b] are valid.  Padded rows are never read as
+ *    keys/values (they may hold anything, NaN included) and produce zeros as
+ *    query rows.  Candidates are packed with device offsets cand_off[B+1].
+ *  - Activations are token-major: q/k/v are [rows][n_heads][d_head], attention
+ *    outputs and hidden states are [rows][d_model], d_model = n_heads * d_head.
+ *
+ * Precision paths
+ *  - CLIMBER_F32 : everything fp32 (reference path; any d_head <= 256).
+ *  - CLIMBER_BF16: bf16 storage, bf16 MFMA products with fp32 accumulation, fp32
+ *    softmax statistics, probabilities rounded to bf16 before the P V product;
+ *    requires d_head == 64, padded history lengths that are multiples of 64 and
+ *    sub_len == 0 or a multiple of 128; the causal flag is not available.
+ */
+#ifndef CLIMBER_H
+#define CLIMBER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CLIMBER_OK 0
+#define CLIMBER_ERR_NULL (-1)        /* a required pointer is NULL */
+#define CLIMBER_ERR_SHAPE (-2)       /* a size is <= 0 or inconsistent (d_model != H*d_head ...) */
+#define CLIMBER_ERR_ALIGN (-3)       /* padding / multiple-of / pointer alignment rule violated */
+#define CLIMBER_ERR_RANGE (-4)       /* layer index, length or offset out of range */
+#define CLIMBER_ERR_TAU (-5)         /* qk_scale / rms_eps not finite or not positive */
+#define CLIMBER_ERR_BUFSIZE (-6)     /* caller buffer (cache, workspace) too small */
+#define CLIMBER_ERR_UNSUPPORTED (-7) /* valid request the selected precision path cannot run */
+#define CLIMBER_ERR_RUNTIME (-8)     /* a HIP runtime call failed (no device, bad stream ...) */
+
+#define CLIMBER_F32 0
+#define CLIMBER_BF16 1
+
+#define CLIMBER_HIST_CAUSAL 1 /* flags bit 0: history token i only sees j <= i of its subsequence */
+
+#define CLIMBER_MODE_HISTORY 0
+#define CLIMBER_MODE_CANDIDATE 1
+
+/* Hyper-parameters.  Plain data, passed by pointer, copied where kept. */
+typedef struct climber_config {
+    int32_t n_layers; /* layers of the stack (>= 1); attention-only use: number of cache layers */
+    int32_t d_model;  /* = n_heads * d_head */
+    int32_t n_heads;
+    int32_t d_head;
+    int32_t d_ffn;    /* feed-forward hidden width; ignored by the attention-only calls */
+    int32_t n_scen;   /* temperature table rows (scenarios) */
+    int32_t n_beh;    /* temperature table columns (behaviours / extraction strategies) */
+    int32_t sub_len;  /* subsequence length n_k of Sec. 3.1.2; 0 = one subsequence */
+    int32_t dtype;    /* CLIMBER_F32 | CLIMBER_BF16 */
+    int32_t flags;    /* CLIMBER_HIST_CAUSAL */
+    float qk_scale;   /* multiplies Q K^T before the temperature divide; Eq. (3) literally = 1 */
+    float rms_eps;    /* epsilon of the RMSNorm in the layer stack */
+} climber_config;
+
+/* One layer's weights: device pointers, row-major, element type = config dtype (bf16 / fp32).
+ *   g1 [d]   gain of the pre-attention RMSNorm      wqkv [d][3d]  columns Q heads | K heads | V heads
+ *   wo [d][d]                                       g2 [d]   gain of the pre-FFN RMSNorm
+ *   w1 [d][d_ffn]                                   w2 [d_ffn][d]
+ * Layer (f_QKV and f_FFN of Eq. (3) made concrete; the paper does not fix these details):
+ *   qkv = RMSNorm(x; g1) wqkv;  o = attention;  h = x + o wo;  y = h + GELU_erf(RMSNorm(h; g2) w1) w2 */
+typedef struct climber_layer_weights {
+    const void *g1, *wqkv, *wo, *g2, *w1, *w2;
+} climber_layer_weights;
+
+typedef struct climber_weights {
+    int32_t n_layers;                    /* must equal config.n_layers */
+    const climber_layer_weights *layers; /* host array of n_layers entries */
+} climber_weights;
+
+/* Opaque host-side handle describing a KV cache that lives in a caller-owned device buffer. */
+typedef struct climber_kv_cache climber_kv_cache;
+
+const char *climber_strerror(int code);
+
+/* ---- KV cache (Sec. 3.2: "multi-layered key-value cache vectors from user features") ----------
+ * The cache holds, for each of config.n_layers layers, the keys and values of every (padded)
+ * history token of the batch, in a layout private to the library (for bf16: MFMA operand
+ * fragments of 32-key blocks, so that the candidate pass streams it with linear 16-byte
+ * accesses; padded slots are stored as zeros).  It is immutable between encodes, so any
+ * number of scoring calls, on any streams, may read it concurrently.
+ */
+
+/* Bytes the device buffer of a cache must have.  hist_len_padded: host [B].  Returns 0 on any
+ * invalid argument. */
+size_t climber_kv_cache_bytes(const climber_config *cfg, int32_t B, const int32_t *hist_len_padded);
+
+/* Create the handle.  hist_len, hist_len_padded: host [B], copied.  dev_buf: dev, `bytes` long,
+ * 256-byte aligned, owned by the caller and must outlive the handle's use.  A small descriptor
+ * (lengths, offsets, schedule) is copied into the head of dev_buf with a synchronous copy; this
+ * is the only call of the library that synchronises.  0 <= hist_len[b] <= hist_len_padded[b];
+ * B >= 1; sum of padded lengths < 2^31 / d_model.
+ * Errors: NULL, SHAPE, ALIGN (padding rule of the dtype), RANGE, BUFSIZE, UNSUPPORTED, RUNTIME. */
+int climber_kv_cache_create(const climber_config *cfg, int32_t B, const int32_t *hist_len,
+                            const int32_t *hist_len_padded, void *dev_buf, size_t bytes,
+                            climber_kv_cache **out);
+
+/* Frees the host handle only; the device buffer stays with the caller.  NULL is accepted. */
+int climber_kv_cache_destroy(climber_kv_cache *cache);
+
+/* Total padded history rows of the batch (= tok_off[B]); negative error code on NULL. */
+int64_t climber_kv_cache_rows(const climber_kv_cache *cache);
+
+/* ---- attention-only entry points (caller supplies Q/K/V of one layer) ------------------------- */
+
+/* History side of one layer (Eq. (3) restricted to a subsequence, Sec. 3.1.2):
+ *  1. stores k, v of all history tokens into cache layer `layer`;
+ *  2. if o_hist != NULL, block-diagonal attention of the history tokens:
+ *       o_i = sum_j softmax_j( qk_scale <q_i,k_j> / tau[scen_i][beh_i] ) v_j
+ *     over the valid tokens j of i's subsequence (j <= i as well under CLIMBER_HIST_CAUSAL).
+ * tau_layer: dev [n_scen][n_beh] fp32.  q (may be NULL iff o_hist is NULL), k, v: dev
+ * [rows][H][d_head] of the config dtype, rows = climber_kv_cache_rows().  scen, beh: dev int32
+ * [rows] (only read when o_hist != NULL).  o_hist: dev [rows][d_model] of the config dtype;
+ * padded rows receive zeros. */
+int climber_attn_history(const climber_config *cfg, const float *tau_layer, const void *q,
+                         const void *k, const void *v, const int32_t *scen, const int32_t *beh,
+                         climber_kv_cache *cache, int32_t layer, void *o_hist, void *stream);
+
+/* SUMI attention of one layer (mask of Sec. 3.2, temperature of Eq. (3)): for candidate c of
+ * user b
+ *     o_c = softmax over { all hist_len[b] cached history keys of b, c's own key } of
+ *           qk_scale <q_c, k> / tau[cscen_c][cbeh_c],   applied to the matching values.
+ * q_c, k_c, v_c: dev [m_total][H][d_head]; cand_off: dev int32 [B+1], cand_off[0] = 0,
+ * non-decreasing, cand_off[B] = m_total; m_max: host value >= max_b (cand_off[b+1]-cand_off[b])
+ * (sizes the launch; a user with more candidates than m_max has the excess left unwritten).
+ * cand_scen, cand_beh: dev int32 [m_total].  o_c: dev [m_total][d_model].
+ * Scoring a candidate set in chunks = calling this repeatedly on the same (const) cache. */
+int climber_attn_sumi(const climber_config *cfg, const float *tau_layer,
+                      const climber_kv_cache *cache, int32_t layer, const void *q_c,
+                      const void *k_c, const void *v_c, const int32_t *cand_off, int32_t m_total,
+                      int32_t m_max, const int32_t *cand_scen, const int32_t *cand_beh, void *o_c,
+                      void *stream);
+
+/* ---- layer stack (CLIMBER_BF16 only) ---------------------------------------------------------- */
+
+/* Bytes of scratch the stack calls need for up to max_rows rows (history rows or candidates). */
+size_t climber_workspace_bytes(const climber_config *cfg, int64_t max_rows);
+
+/* One layer of the stack on the history rows (mode HISTORY: writes cache layer `layer`, attends
+ * block-diagonally) or on candidate rows (mode CANDIDATE: SUMI attention against cache layer
+ * `layer`).  x_in, x_out: dev fp32 [rows][d_model] residual stream (x_out may be NULL in HISTORY
+ * mode: then only the layer's K/V are produced, which is all the last layer of an encode needs;
+ * x_out may alias x_in).  ids: per-row scenario / behaviour ids of the rows being processed.
+ * cand_off / m_total / m_max as in climber_attn_sumi (ignored in HISTORY mode).
+ * workspace: dev, >= climber_workspace_bytes(cfg, rows), 256-byte aligned. */
+int climber_layer_forward(const climber_config *cfg, const climber_layer_weights *w,
+                          const float *tau_layer, int32_t layer, int32_t mode,
+                          climber_kv_cache *cache, const float *x_in, float *x_out,
+                          const int32_t *scen, const int32_t *beh, const int32_t *cand_off,
+                          int32_t m_total, int32_t m_max, void *workspace, size_t ws_bytes,
+                          void *stream);
+
+/* History encode (first phase of the serving flow, Sec. 3.2): runs the packed history embeddings
+ * x_hist (dev bf16 [rows][d_model]) through all layers and fills every layer of the cache.  The
+ * last layer stops after its K/V are stored.  tau: dev fp32 [n_layers][n_scen][n_beh].
+ * workspace must hold climber_workspace_bytes(cfg, rows). */
+int climber_history_encode(const climber_config *cfg, const climber_weights *weights,
+                           const float *tau, const void *x_hist, const int32_t *scen,
+                           const int32_t *beh, climber_kv_cache *cache, void *workspace,
+                           size_t ws_bytes, void *stream);
+
+/* Candidate scoring (second phase): x_cand dev bf16 [m_total][d_model] -> y_cand dev fp32
+ * [m_total][d_model], the candidates' final-layer hidden states (the paper's scalar score needs
+ * its fusion module and an unspecified head on top of these).  workspace must hold
+ * climber_workspace_bytes(cfg, m_total). */
+int climber_sumi_score(const climber_config *cfg, const climber_weights *weights, const float *tau,
+                       const climber_kv_cache *cache, const void *x_cand, const int32_t *cand_off,
+                       int32_t m_total, int32_t m_max, const int32_t *cand_scen,
+                       const int32_t *cand_beh, float *y_cand, void *workspace, size_t ws_bytes,
+                       void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLIMBER_H */

@@ -1,0 +1,24 @@
+// Internal interface between the C-ABI translation unit and the layer-stack driver.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/climber.h"
+
+namespace climber {
+
+// Attention with explicit row strides (q, k, v share one stride: they are column blocks of one
+// fused projection output in the stack, dense arrays in the attention-only calls).
+int attn_history_strided(const climber_config *cfg, const float *tau_layer, const void *q,
+                         const void *k, const void *v, int64_t ld, const int32_t *scen,
+                         const int32_t *beh, climber_kv_cache *cache, int32_t layer, void *o,
+                         int64_t ld_o, hipStream_t s);
+int attn_sumi_strided(const climber_config *cfg, const float *tau_layer,
+                      const climber_kv_cache *cache, int32_t layer, const void *q, const void *k,
+                      const void *v, int64_t ld, const int32_t *cand_off, int32_t m_total,
+                      int32_t m_max, const int32_t *cscen, const int32_t *cbeh, void *o,
+                      int64_t ld_o, hipStream_t s);
+int64_t cache_rows(const climber_kv_cache *c);
+int check_stack_call(const climber_config *cfg, const climber_kv_cache *cache, int32_t layer);
+
+}  // namespace climber

@@ -1,0 +1,126 @@
+"""Shared plumbing of the GPU parity tests: run a workload through the C-ABI binding, run the same
+arrays through the oracle, compare.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+
+import oracle
+import workloads as W
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def torch_dtype(spec_dtype):
+    import torch
+    return torch.bfloat16 if spec_dtype == "bf16" else torch.float32
+
+
+def make_config(spec, n_layers=1, causal=False):
+    import paper_2502_09888_amd as P
+    return P.Config(n_layers=n_layers, n_heads=spec.H, d_head=spec.dh, n_scen=spec.n_scen,
+                    n_beh=spec.n_beh, sub_len=spec.sub_len,
+                    dtype=P.BF16 if spec.dtype == "bf16" else P.F32,
+                    flags=1 if causal else 0, qk_scale=spec.qk_scale)
+
+
+class GpuAttention:
+    """Device copies of one attention workload + a KV cache created for it."""
+
+    def __init__(self, w, causal=False):
+        import torch
+        import paper_2502_09888_amd as P
+        self.P, self.torch, self.w = P, torch, w
+        spec = w["spec"]
+        self.spec = spec
+        self.cfg = make_config(spec, causal=causal)
+        dt = torch_dtype(spec.dtype)
+        dev = "cuda:0"
+        self.dt = dt
+        for n in ("qh", "kh", "vh", "qc", "kc", "vc"):
+            setattr(self, n, torch.from_numpy(w[n]).to(dev).to(dt).contiguous())
+        for n in ("scen", "beh", "cscen", "cbeh", "cand_off"):
+            setattr(self, n, torch.from_numpy(w[n]).to(dev))
+        self.tau = torch.from_numpy(w["tau"]).to(dev)
+        self.padded = [int(x) for x in np.diff(w["tok_off"])]
+        nbytes = P.climber_kv_cache_bytes(self.cfg, self.padded)
+        assert nbytes > 0
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        self.cache = P.climber_kv_cache_create(self.cfg, [int(x) for x in w["hist_len"]],
+                                               self.padded, self.buf)
+        self.d = spec.H * spec.dh
+
+    def history(self, want_output=True):
+        t = self.torch
+        o = t.full((self.qh.shape[0], self.d), float("nan"), dtype=self.dt, device="cuda:0") \
+            if want_output else None
+        self.P.climber_attn_history(self.cfg, self.tau, self.qh, self.kh, self.vh, self.scen,
+                                    self.beh, self.cache, 0, o)
+        t.cuda.synchronize()
+        return None if o is None else o.float().cpu().numpy()
+
+    def sumi(self, sel=None):
+        """Score all candidates (sel None) or, per user, the candidate sub-range sel=(lo, hi)."""
+        t, w = self.torch, self.w
+        if sel is None:
+            qc, kc, vc, cs, cb, off = self.qc, self.kc, self.vc, self.cscen, self.cbeh, self.cand_off
+            off_h = w["cand_off"]
+        else:
+            idx, cnt = [], []
+            for b in range(self.spec.B):
+                c0, c1 = int(w["cand_off"][b]), int(w["cand_off"][b + 1])
+                lo, hi = min(c0 + sel[0], c1), min(c0 + sel[1], c1)
+                idx.extend(range(lo, hi))
+                cnt.append(hi - lo)
+            self.last_idx = np.array(idx, dtype=np.int64)
+            ii = t.from_numpy(self.last_idx).to("cuda:0")
+            qc, kc, vc = (x[ii].contiguous() for x in (self.qc, self.kc, self.vc))
+            cs, cb = self.cscen[ii].contiguous(), self.cbeh[ii].contiguous()
+            off_h = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int32)
+            off = t.from_numpy(off_h).to("cuda:0")
+        m_total = int(off_h[-1])
+        m_max = int(np.diff(off_h).max()) if m_total else 0
+        o = t.full((max(m_total, 1), self.d), float("nan"), dtype=self.dt, device="cuda:0")
+        self.P.climber_attn_sumi(self.cfg, self.tau, self.cache, 0, qc, kc, vc, off, m_total, m_max,
+                                 cs, cb, o)
+        t.cuda.synchronize()
+        return o[:m_total].float().cpu().numpy()
+
+
+def oracle_history(w, causal=False):
+    s = w["spec"]
+    return oracle.attn_history(w["tok_off"], w["hist_len"], w["qh"], w["kh"], w["vh"], w["scen"],
+                               w["beh"], w["tau"], s.qk_scale, sub_len=s.sub_len, causal=causal)
+
+
+def oracle_sumi(w, users=None):
+    """Oracle SUMI output for all users or for a list of users (rows concatenated in that order)."""
+    s = w["spec"]
+    if users is None:
+        return oracle.attn_sumi(w["tok_off"], w["hist_len"], w["cand_off"], w["kh"], w["vh"],
+                                w["qc"], w["kc"], w["vc"], w["cscen"], w["cbeh"], w["tau"],
+                                s.qk_scale)
+    outs = []
+    for b in users:
+        t0, t1 = int(w["tok_off"][b]), int(w["tok_off"][b + 1])
+        c0, c1 = int(w["cand_off"][b]), int(w["cand_off"][b + 1])
+        outs.append(oracle.attn_sumi([0, t1 - t0], [w["hist_len"][b]], [0, c1 - c0],
+                                     w["kh"][t0:t1], w["vh"][t0:t1], w["qc"][c0:c1], w["kc"][c0:c1],
+                                     w["vc"][c0:c1], w["cscen"][c0:c1], w["cbeh"][c0:c1], w["tau"],
+                                     s.qk_scale))
+    return np.concatenate(outs)
+
+
+def valid_rows(w):
+    m = np.zeros(int(w["tok_off"][-1]), bool)
+    for b in range(len(w["hist_len"])):
+        m[w["tok_off"][b]:w["tok_off"][b] + w["hist_len"][b]] = True
+    return m
+
+
+def max_abs(a, b):
+    return float(np.max(np.abs(np.asarray(a, np.float64) - np.asarray(b, np.float64)))) if a.size else 0.0
