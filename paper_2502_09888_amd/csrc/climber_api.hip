@@ -170,6 +170,13 @@ int attn_sumi_strided(const climber_config *cfg, const float *tau_layer,
 
 int64_t cache_rows(const climber_kv_cache *c) { return c->rows; }
 
+int check_stack_call(const climber_config *cfg, const climber_kv_cache *cache, int32_t layer)
+{
+    int e = check_config(cfg);
+    if (e) return e;
+    return check_cache_use(cfg, cache, layer);
+}
+
 }  // namespace climber
 
 // ---- C ABI ------------------------------------------------------------------------------------

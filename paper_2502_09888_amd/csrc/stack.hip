@@ -1,8 +1,214 @@
-// Layer-stack driver (placeholder until the MFMA GEMMs land).
+// Layer-stack driver: the serving flow of Climber (arXiv 2502.09888, Sec. 3.2) over the full
+// layers -- history encode (fills every layer of the KV cache) and candidate scoring against it.
+// Layer composition (the paper leaves f_QKV / f_FFN of Eq. (3) open; this build fixes it):
+//   qkv = RMSNorm(x; g1) Wqkv;  o = attention;  h = x + o Wo;  y = h + GELU(RMSNorm(h; g2) W1) W2
+// The residual stream is fp32, GEMM operands are bf16, accumulation is fp32.
 #include "stack.h"
-extern "C" {
-size_t climber_workspace_bytes(const climber_config *, int64_t) { return 0; }
-int climber_layer_forward(const climber_config *, const climber_layer_weights *, const float *, int32_t, int32_t, climber_kv_cache *, const float *, float *, const int32_t *, const int32_t *, const int32_t *, int32_t, int32_t, void *, size_t, void *) { return CLIMBER_ERR_UNSUPPORTED; }
-int climber_history_encode(const climber_config *, const climber_weights *, const float *, const void *, const int32_t *, const int32_t *, climber_kv_cache *, void *, size_t, void *) { return CLIMBER_ERR_UNSUPPORTED; }
-int climber_sumi_score(const climber_config *, const climber_weights *, const float *, const climber_kv_cache *, const void *, const int32_t *, int32_t, int32_t, const int32_t *, const int32_t *, float *, void *, size_t, void *) { return CLIMBER_ERR_UNSUPPORTED; }
+
+#include <algorithm>
+#include <cmath>
+
+#include "gemm.h"
+
+using namespace climber;
+
+namespace {
+
+size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+struct Workspace {
+    float *x32;     // [rows][d]   residual stream of encode / score
+    float *h32;     // [rows][d]   post-attention residual
+    uint8_t *xn;    // [rows][d]   bf16 normalised rows
+    uint8_t *qkv;   // [rows][3d]  bf16 fused projection output
+    uint8_t *o;     // [rows][d]   bf16 attention output
+    uint8_t *u;     // [rows][F]   bf16 FFN hidden
+    uint8_t *wpack; // packed weight of the GEMM in flight (largest of the four)
+    size_t total;
+};
+
+Workspace carve(const climber_config *c, int64_t rows, void *base)
+{
+    const size_t d = c->d_model, F = c->d_ffn, n = (size_t)rows;
+    uint8_t *p = (uint8_t *)base;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { uint8_t *q = p + off; off += up256(bytes); return q; };
+    Workspace w;
+    w.x32 = (float *)take(n * d * 4);
+    w.h32 = (float *)take(n * d * 4);
+    w.xn = take(n * d * 2);
+    w.qkv = take(n * 3 * d * 2);
+    w.o = take(n * d * 2);
+    w.u = take(n * F * 2);
+    const size_t wmax = std::max((size_t)3 * d * d, d * F) * 2;
+    w.wpack = take(wmax);
+    w.total = off;
+    return w;
 }
+
+int check_stack_config(const climber_config *c)
+{
+    if (!c) return CLIMBER_ERR_NULL;
+    if (c->dtype != CLIMBER_BF16) return CLIMBER_ERR_UNSUPPORTED;
+    if (c->d_ffn < 1) return CLIMBER_ERR_SHAPE;
+    if (c->d_model % 128 != 0 || c->d_ffn % 128 != 0) return CLIMBER_ERR_UNSUPPORTED;
+    if (!(c->rms_eps > 0.f) || !std::isfinite(c->rms_eps)) return CLIMBER_ERR_TAU;
+    return CLIMBER_OK;
+}
+
+int rt(hipError_t e) { return e == hipSuccess ? CLIMBER_OK : CLIMBER_ERR_RUNTIME; }
+
+#define TRY(x)            \
+    do {                  \
+        int e_ = (x);     \
+        if (e_) return e_; \
+    } while (0)
+
+// one layer on `rows` rows; ws.x32 is not touched here
+int run_layer(const climber_config *cfg, const climber_layer_weights *w, const float *tau_layer,
+              int32_t layer, int32_t mode, climber_kv_cache *cache, const float *x_in, float *x_out,
+              const int32_t *scen, const int32_t *beh, const int32_t *cand_off, int32_t m_total,
+              int32_t m_max, int64_t rows, const Workspace &ws, hipStream_t s)
+{
+    const int d = cfg->d_model, F = cfg->d_ffn, M = (int)rows;
+    TRY(rt(rmsnorm_to_bf16(x_in, w->g1, ws.xn, rows, d, cfg->rms_eps, s)));
+    TRY(rt(pack_weight(w->wqkv, ws.wpack, d, 3 * d, s)));
+    TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xn, d, ws.wpack, M, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, s)));
+    const uint8_t *q = ws.qkv, *k = ws.qkv + (size_t)d * 2, *v = ws.qkv + (size_t)2 * d * 2;
+    if (mode == CLIMBER_MODE_HISTORY) {
+        TRY(attn_history_strided(cfg, tau_layer, q, k, v, 3 * d, scen, beh, cache, layer,
+                                 x_out ? ws.o : nullptr, d, s));
+        if (!x_out) return CLIMBER_OK;
+    } else {
+        TRY(attn_sumi_strided(cfg, tau_layer, cache, layer, q, k, v, 3 * d, cand_off, m_total, m_max,
+                              scen, beh, ws.o, d, s));
+    }
+    TRY(rt(pack_weight(w->wo, ws.wpack, d, d, s)));
+    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o, d, ws.wpack, M, d, d, ws.h32, d, x_in, d, s)));
+    TRY(rt(rmsnorm_to_bf16(ws.h32, w->g2, ws.xn, rows, d, cfg->rms_eps, s)));
+    TRY(rt(pack_weight(w->w1, ws.wpack, d, F, s)));
+    TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xn, d, ws.wpack, M, F, d, ws.u, F, nullptr, 0, s)));
+    TRY(rt(pack_weight(w->w2, ws.wpack, F, d, s)));
+    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.u, F, ws.wpack, M, d, F, x_out, d, ws.h32, d, s)));
+    return CLIMBER_OK;
+}
+
+int check_layer_weights(const climber_layer_weights *w)
+{
+    if (!w || !w->g1 || !w->wqkv || !w->wo || !w->g2 || !w->w1 || !w->w2) return CLIMBER_ERR_NULL;
+    const void *ps[] = {w->g1, w->wqkv, w->wo, w->g2, w->w1, w->w2};
+    for (const void *p : ps)
+        if ((uintptr_t)p % 16 != 0) return CLIMBER_ERR_ALIGN;
+    return CLIMBER_OK;
+}
+
+int check_cand_args(const climber_config *cfg, const int32_t *cand_off, int32_t m_total, int32_t m_max)
+{
+    if (!cand_off) return CLIMBER_ERR_NULL;
+    if (m_total < 0 || m_max < 0 || m_max > m_total || (m_total > 0 && m_max == 0))
+        return CLIMBER_ERR_SHAPE;
+    if ((int64_t)m_total * std::max(cfg->d_ffn, 3 * cfg->d_model) >= (int64_t)1 << 31)
+        return CLIMBER_ERR_RANGE;
+    return CLIMBER_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t climber_workspace_bytes(const climber_config *cfg, int64_t max_rows)
+{
+    if (check_stack_config(cfg) != CLIMBER_OK || max_rows < 0) return 0;
+    return carve(cfg, max_rows, nullptr).total;
+}
+
+int climber_layer_forward(const climber_config *cfg, const climber_layer_weights *w,
+                          const float *tau_layer, int32_t layer, int32_t mode,
+                          climber_kv_cache *cache, const float *x_in, float *x_out,
+                          const int32_t *scen, const int32_t *beh, const int32_t *cand_off,
+                          int32_t m_total, int32_t m_max, void *workspace, size_t ws_bytes,
+                          void *stream)
+{
+    TRY(check_stack_config(cfg));
+    TRY(check_stack_call(cfg, cache, layer));
+    TRY(check_layer_weights(w));
+    if (mode != CLIMBER_MODE_HISTORY && mode != CLIMBER_MODE_CANDIDATE) return CLIMBER_ERR_SHAPE;
+    if (!tau_layer || !x_in || !scen || !beh || !workspace) return CLIMBER_ERR_NULL;
+    if (mode == CLIMBER_MODE_CANDIDATE) {
+        if (!x_out) return CLIMBER_ERR_NULL;
+        TRY(check_cand_args(cfg, cand_off, m_total, m_max));
+    }
+    const int64_t rows = mode == CLIMBER_MODE_HISTORY ? cache_rows(cache) : m_total;
+    if (rows * (int64_t)std::max(cfg->d_ffn, 3 * cfg->d_model) >= (int64_t)1 << 31)
+        return CLIMBER_ERR_RANGE;
+    if ((uintptr_t)workspace % 256 != 0 || (uintptr_t)x_in % 16 != 0 || (uintptr_t)x_out % 16 != 0)
+        return CLIMBER_ERR_ALIGN;
+    const Workspace ws = carve(cfg, rows, workspace);
+    if (ws_bytes < ws.total) return CLIMBER_ERR_BUFSIZE;
+    if (rows == 0) return CLIMBER_OK;
+    return run_layer(cfg, w, tau_layer, layer, mode, cache, x_in, x_out, scen, beh, cand_off, m_total,
+                     m_max, rows, ws, (hipStream_t)stream);
+}
+
+int climber_history_encode(const climber_config *cfg, const climber_weights *weights,
+                           const float *tau, const void *x_hist, const int32_t *scen,
+                           const int32_t *beh, climber_kv_cache *cache, void *workspace,
+                           size_t ws_bytes, void *stream)
+{
+    TRY(check_stack_config(cfg));
+    TRY(check_stack_call(cfg, cache, 0));
+    if (!weights || !weights->layers || !tau || !x_hist || !scen || !beh || !workspace)
+        return CLIMBER_ERR_NULL;
+    if (weights->n_layers != cfg->n_layers) return CLIMBER_ERR_SHAPE;
+    for (int l = 0; l < cfg->n_layers; ++l) TRY(check_layer_weights(&weights->layers[l]));
+    const int64_t rows = cache_rows(cache);
+    if (rows * (int64_t)std::max(cfg->d_ffn, 3 * cfg->d_model) >= (int64_t)1 << 31)
+        return CLIMBER_ERR_RANGE;
+    if ((uintptr_t)workspace % 256 != 0 || (uintptr_t)x_hist % 16 != 0) return CLIMBER_ERR_ALIGN;
+    const Workspace ws = carve(cfg, rows, workspace);
+    if (ws_bytes < ws.total) return CLIMBER_ERR_BUFSIZE;
+    if (rows == 0) return CLIMBER_OK;
+    hipStream_t s = (hipStream_t)stream;
+    TRY(rt(cast_bf16_to_f32(x_hist, ws.x32, rows * cfg->d_model, s)));
+    const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const bool last = l + 1 == cfg->n_layers;  // nothing reads the last layer's history output
+        TRY(run_layer(cfg, &weights->layers[l], tau + l * tl, l, CLIMBER_MODE_HISTORY, cache, ws.x32,
+                      last ? nullptr : ws.x32, scen, beh, nullptr, 0, 0, rows, ws, s));
+    }
+    return CLIMBER_OK;
+}
+
+int climber_sumi_score(const climber_config *cfg, const climber_weights *weights, const float *tau,
+                       const climber_kv_cache *cache, const void *x_cand, const int32_t *cand_off,
+                       int32_t m_total, int32_t m_max, const int32_t *cand_scen,
+                       const int32_t *cand_beh, float *y_cand, void *workspace, size_t ws_bytes,
+                       void *stream)
+{
+    TRY(check_stack_config(cfg));
+    TRY(check_stack_call(cfg, cache, 0));
+    if (!weights || !weights->layers || !tau || !x_cand || !cand_scen || !cand_beh || !y_cand ||
+        !workspace)
+        return CLIMBER_ERR_NULL;
+    if (weights->n_layers != cfg->n_layers) return CLIMBER_ERR_SHAPE;
+    for (int l = 0; l < cfg->n_layers; ++l) TRY(check_layer_weights(&weights->layers[l]));
+    TRY(check_cand_args(cfg, cand_off, m_total, m_max));
+    if ((uintptr_t)workspace % 256 != 0 || (uintptr_t)x_cand % 16 != 0 || (uintptr_t)y_cand % 16 != 0)
+        return CLIMBER_ERR_ALIGN;
+    const Workspace ws = carve(cfg, m_total, workspace);
+    if (ws_bytes < ws.total) return CLIMBER_ERR_BUFSIZE;
+    if (m_total == 0) return CLIMBER_OK;
+    hipStream_t s = (hipStream_t)stream;
+    TRY(rt(cast_bf16_to_f32(x_cand, ws.x32, (int64_t)m_total * cfg->d_model, s)));
+    const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const bool last = l + 1 == cfg->n_layers;
+        // the cache is only read in candidate mode
+        TRY(run_layer(cfg, &weights->layers[l], tau + l * tl, l, CLIMBER_MODE_CANDIDATE,
+                      const_cast<climber_kv_cache *>(cache), ws.x32, last ? y_cand : ws.x32,
+                      cand_scen, cand_beh, cand_off, m_total, m_max, m_total, ws, s));
+    }
+    return CLIMBER_OK;
+}
+
+}  // extern "C"

@@ -124,3 +124,77 @@ def valid_rows(w):
 
 def max_abs(a, b):
     return float(np.max(np.abs(np.asarray(a, np.float64) - np.asarray(b, np.float64)))) if a.size else 0.0
+
+
+# ------------------------------------------------------------------ layer stack
+def stack_config(spec):
+    import paper_2502_09888_amd as P
+    return P.Config(n_layers=spec.n_layers, d_model=spec.d_model, n_heads=spec.H, d_head=spec.dh,
+                    d_ffn=spec.d_ffn, n_scen=spec.n_scen, n_beh=spec.n_beh, sub_len=spec.sub_len,
+                    dtype=P.BF16, qk_scale=spec.qk_scale, rms_eps=spec.rms_eps)
+
+
+def oracle_stack_config(spec):
+    return oracle.StackConfig(spec.n_layers, spec.d_model, spec.H, spec.dh, spec.d_ffn, spec.n_scen,
+                              spec.n_beh, sub_len=spec.sub_len, qk_scale=spec.qk_scale,
+                              rms_eps=spec.rms_eps)
+
+
+class GpuStack:
+    """Device copies of one full-stack workload, cache and workspace."""
+
+    def __init__(self, w):
+        import torch
+        import paper_2502_09888_amd as P
+        self.P, self.torch, self.w = P, torch, w
+        spec = w["spec"]
+        self.spec, self.cfg = spec, stack_config(spec)
+        dev, bf = "cuda:0", torch.bfloat16
+        self.layers = [{n.lower(): torch.from_numpy(lw[n]).to(dev).to(bf).contiguous()
+                        for n in ("g1", "Wqkv", "Wo", "g2", "W1", "W2")} for lw in w["layers"]]
+        self.x_hist = torch.from_numpy(w["x_hist"]).to(dev).to(bf)
+        self.x_cand = torch.from_numpy(w["x_cand"]).to(dev).to(bf)
+        for n in ("scen", "beh", "cscen", "cbeh", "cand_off"):
+            setattr(self, n, torch.from_numpy(w[n]).to(dev))
+        self.tau = torch.from_numpy(w["tau"]).to(dev)
+        self.padded = [int(x) for x in np.diff(w["tok_off"])]
+        self.buf = torch.empty(P.climber_kv_cache_bytes(self.cfg, self.padded), dtype=torch.uint8,
+                               device=dev)
+        self.cache = P.climber_kv_cache_create(self.cfg, [int(x) for x in w["hist_len"]],
+                                               self.padded, self.buf)
+        rows = max(int(w["tok_off"][-1]), int(w["cand_off"][-1]))
+        self.ws = torch.empty(P.climber_workspace_bytes(self.cfg, rows), dtype=torch.uint8, device=dev)
+        self.m_total = int(w["cand_off"][-1])
+        self.m_max = int(np.diff(w["cand_off"]).max())
+
+    def encode(self):
+        self.P.climber_history_encode(self.cfg, self.layers, self.tau, self.x_hist, self.scen,
+                                      self.beh, self.cache, self.ws)
+
+    def score(self):
+        t = self.torch
+        y = t.full((self.m_total, self.spec.d_model), float("nan"), dtype=t.float32, device="cuda:0")
+        self.P.climber_sumi_score(self.cfg, self.layers, self.tau, self.cache, self.x_cand,
+                                  self.cand_off, self.m_total, self.m_max, self.cscen, self.cbeh, y,
+                                  self.ws)
+        t.cuda.synchronize()
+        return y.cpu().numpy()
+
+
+def oracle_stack_users(w, users):
+    """Oracle encode + score for selected users, each on its own.  Returns (y_cand rows
+    concatenated in that order, list of per-user y_hist)."""
+    spec = w["spec"]
+    cfg = oracle_stack_config(spec)
+    ys, yhs = [], []
+    for b in users:
+        t0, t1 = int(w["tok_off"][b]), int(w["tok_off"][b + 1])
+        c0, c1 = int(w["cand_off"][b]), int(w["cand_off"][b + 1])
+        kc, vc, yh = oracle.stack_encode(cfg, w["layers"], w["tau"], [0, t1 - t0],
+                                         [w["hist_len"][b]], w["x_hist"][t0:t1], w["scen"][t0:t1],
+                                         w["beh"][t0:t1])
+        ys.append(oracle.stack_score(cfg, w["layers"], w["tau"], [0, t1 - t0], [w["hist_len"][b]],
+                                     kc, vc, [0, c1 - c0], w["x_cand"][c0:c1], w["cscen"][c0:c1],
+                                     w["cbeh"][c0:c1]))
+        yhs.append(yh)
+    return np.concatenate(ys), yhs
