@@ -1,0 +1,117 @@
+"""Host-side checks that need no GPU: the built library exports every entry point the header
+declares, and argument validation rejects bad calls before anything would be launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2502_09888_amd as P
+from paper_2502_09888_amd import build as hip_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000  # 256-byte aligned, never dereferenced on the host
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    if not os.path.exists(P.library_path()):
+        hip_build.build()
+    return P.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "climber.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(climber_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(_lib):
+    names = declared_functions()
+    assert {"climber_history_encode", "climber_sumi_score", "climber_layer_forward",
+            "climber_attn_sumi", "climber_attn_history", "climber_kv_cache_create"} <= set(names)
+    for n in names:
+        assert hasattr(_lib, n), n
+    # the Python binding carries the same names
+    for n in names:
+        assert hasattr(P, n), n
+
+
+def cfg(**kw):
+    base = dict(n_layers=1, n_heads=4, d_head=64, n_scen=8, n_beh=4, sub_len=128, dtype=P.BF16,
+                qk_scale=0.125)
+    base.update(kw)
+    return P.Config(**base)
+
+
+def create(c, hist_len, padded, buf=FAKE, nbytes=1 << 40):
+    out = C.c_void_p()
+    arr = lambda xs: (C.c_int32 * len(xs))(*xs)
+    rc = P.load_library().climber_kv_cache_create(C.byref(c), len(hist_len), arr(hist_len),
+                                                  arr(padded), buf, nbytes, C.byref(out))
+    assert rc != 0 and not out.value
+    return rc
+
+
+def test_strerror_names_every_code():
+    seen = {P.climber_strerror(c) for c in range(0, -9, -1)}
+    assert len(seen) == 9 and "unknown" not in " ".join(seen)
+    assert "unknown" in P.climber_strerror(-99)
+
+
+def test_cache_bytes():
+    c = cfg()
+    # header + 2 (K,V) * rows * d_model * 2 bytes
+    assert P.climber_kv_cache_bytes(c, [512] * 32) == 512 + 2 * 32 * 512 * 256 * 2
+    assert P.climber_kv_cache_bytes(c, [100]) == 0            # bf16 padding rule
+    assert P.climber_kv_cache_bytes(cfg(d_head=32), [128]) == 0
+    assert P.climber_kv_cache_bytes(cfg(dtype=P.F32, d_head=32, sub_len=7), [100]) > 0
+
+
+def test_create_rejects_bad_arguments():
+    assert create(cfg(qk_scale=0.0), [64], [64]) == -5
+    assert create(cfg(qk_scale=float("nan")), [64], [64]) == -5
+    assert create(cfg(d_head=32), [64], [64]) == -7           # bf16 path needs d_head 64
+    assert create(cfg(flags=1), [64], [64]) == -7             # causal flag: fp32 path only
+    assert create(cfg(sub_len=96), [64], [64]) == -3
+    assert create(cfg(d_model=100), [64], [64]) == -2
+    assert create(cfg(n_scen=0), [64], [64]) == -2
+    assert create(cfg(), [64], [100]) == -3                   # padding not a multiple of 64
+    assert create(cfg(), [65], [64]) == -4                    # valid length beyond padding
+    assert create(cfg(), [-1], [64]) == -4
+    assert create(cfg(), [64], [64], buf=None) == -1
+    assert create(cfg(), [64], [64], buf=FAKE + 8) == -3
+    assert create(cfg(), [64], [64], nbytes=1024) == -6
+    assert create(cfg(dtype=P.F32, d_head=300, sub_len=0), [64], [64]) == -7
+    assert create(cfg(dtype=P.F32, d_head=32, sub_len=0), [20000], [20000]) == -7
+
+
+def test_compute_calls_reject_missing_cache_and_pointers():
+    lib = P.load_library()
+    c = cfg()
+    assert lib.climber_attn_sumi(C.byref(c), FAKE, None, 0, FAKE, FAKE, FAKE, FAKE, 8, 8, FAKE, FAKE,
+                                 FAKE, None) == -1
+    assert lib.climber_attn_history(C.byref(c), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, FAKE,
+                                    None) == -1
+    assert lib.climber_attn_sumi(None, FAKE, None, 0, FAKE, FAKE, FAKE, FAKE, 8, 8, FAKE, FAKE, FAKE,
+                                 None) == -1
+
+
+def test_workspace_bytes():
+    c4 = P.Config(n_layers=4, n_heads=8, d_head=64, d_ffn=2048, n_scen=8, n_beh=4, sub_len=256)
+    n = 32768
+    need = n * 512 * (4 + 4 + 2 + 6 + 2) + n * 2048 * 2 + 2 * max(3 * 512 * 512, 512 * 2048)
+    got = P.climber_workspace_bytes(c4, n)
+    assert need <= got <= need + 8 * 256
+    assert P.climber_workspace_bytes(cfg(dtype=P.F32, d_head=32, sub_len=0), 10) == 0
+    assert P.climber_workspace_bytes(P.Config(n_heads=8, d_head=64, d_ffn=100), 10) == 0
+    assert P.climber_workspace_bytes(P.Config(n_heads=8, d_head=64, d_ffn=256, rms_eps=0.0), 10) == 0
+
+
+def test_binding_has_no_cpu_fallback(monkeypatch, tmp_path):
+    # a missing library must fail loudly, not route anywhere else
+    from paper_2502_09888_amd import climber as mod
+    monkeypatch.setattr(mod, "_lib", None)
+    monkeypatch.setattr(mod, "_LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        mod.load_library()
