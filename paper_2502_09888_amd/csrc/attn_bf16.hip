@@ -6,19 +6,31 @@
 // Shape of the computation (one workgroup = one (user, head, tile of NW*64 query rows)):
 //   - the transposed problem is computed: S^T = K Q^T and O^T = V^T P^T with
 //     v_mfma_f32_32x32x16_bf16.  In the accumulator layout of that instruction a lane owns ONE
-//     query column (lane % 32), so the softmax statistics of a query are per-lane scalars, the
-//     row max / row sum are in-register reductions plus one exchange between the two half-waves,
-//     and the probabilities leave the S^T accumulator already in the B-operand layout the P V
-//     product needs (the cache stores V with the matching key permutation).
-//   - history K/V tiles of 64 keys are copied HBM -> LDS linearly (the cache is stored as MFMA
-//     fragments) into a double buffer and are reused by every wave, i.e. by the whole query tile.
-//   - online softmax in the exp2 domain: p = exp2(s*c - m*c) with c = qk_scale*log2(e)/tau_row,
-//     one FMA + one v_exp_f32 per logit; the reference maximum m is only moved (and O, l
-//     rescaled) when a row maximum exceeds it by more than 2^8 in the exp2 domain, so the rescale
-//     is rare; results are exact because O and l always share the same reference.
-//   - SUMI: the candidate's own key/value initialise the running state (m = own logit, l = 1,
-//     O = own value), which is the "+ itself" term of the mask.
+//     query column (lane % 32), so the softmax statistics of a query are per-lane scalars and the
+//     probabilities leave the S^T accumulator already in the B-operand layout the P V product
+//     needs (the cache stores V with the matching key permutation).
+//   - history K/V tiles of 64 keys are copied HBM -> LDS directly (global_load_lds, no register
+//     staging; the cache is stored as MFMA fragments so the copy is linear) into a ring of 4
+//     buffers, three tiles in flight ahead of the one being computed, and are reused by every
+//     wave, i.e. by the whole query tile.
+//   - FAST pass.  Softmax does not depend on the reference subtracted from the logits as long as
+//     numerator and denominator share it, and fp32 / bf16 carry 8 exponent bits, so for logits of
+//     ordinary size NO reference is needed at all: with the per-row temperature folded into the
+//     query, q' = bf16(q * qk_scale*log2(e)/tau_row), a logit is t = <q',k> straight out of the
+//     MFMA, p = exp2(t), and it costs one v_exp_f32, half a v_cvt_pk_bf16_f32 and half a v_dot2
+//     (denominator) -- no row maximum, no subtraction, no rescale of O.  The loop is software
+//     pipelined over 32-key blocks: the S^T MFMAs of block i+1 are issued before the exponentials
+//     of block i, so matrix and vector pipes overlap inside one wave.
+//   - SAFE pass.  If any row's denominator leaves [2^-40, 2^40] (or is not finite) the workgroup
+//     redoes its work with the classical online softmax: unscaled q, fp32 scale
+//     p = exp2(s*c - m*c), running row maximum (moved when exceeded by 2^8, O and l rescaled).
+//     This covers logits of any size exactly; it is never taken for unit-scale inputs.
+//   - SUMI: the candidate's own key/value initialise the running state, which is the "+ itself"
+//     term of the mask.
 #include "internal.h"
+
+#include <cstdlib>
+#include <type_traits>
 
 namespace climber {
 namespace {
@@ -27,10 +39,15 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
+typedef const __attribute__((address_space(1))) uint8_t glb_u8;
 
-constexpr int kTileKeys = 64;                  // keys per LDS tile = 2 cache blocks
-constexpr int kTileBytes = 2 * kBlockBytes;    // 16 KiB
-constexpr float kRescaleThreshold = 8.0f;      // exp2-domain slack before the reference max moves
+constexpr int kTileKeys = 64;                // keys per LDS tile = 2 cache blocks
+constexpr int kTileBytes = 2 * kBlockBytes;  // 16 KiB
+constexpr int kStages = 4;                   // LDS ring: 3 tiles in flight ahead of the computed one
+constexpr float kSafeSlack = 8.0f;           // SAFE: exp2-domain slack before the row maximum moves
+constexpr float kDenomHi = 1.0e12f;          // FAST is accepted iff kDenomLo < denominator < kDenomHi
+constexpr float kDenomLo = 1.0e-12f;
 
 struct KParams {
     const uint8_t *layer_base;
@@ -44,15 +61,172 @@ struct KParams {
     float scale_log2e;
 };
 
+// Per-wave softmax state for 64 queries (two 32-query blocks).
+struct QState {
+    bf16x8 qf[2][4];  // B operands of S^T: FAST q' = bf16(q*c), SAFE q; [query][16s + 8hf + 0..7]
+    float c[2];       // qk_scale * log2(e) / tau_row                       (SAFE)
+    float m_ref[2];   // running reference maximum, raw logit units         (SAFE)
+    float l[2];       // this half-wave's share of the softmax denominator
+    f32x16 O[2][2];   // O^T[d block][query block]
+};
+
+struct KFrags { bf16x8 a[4]; };  // K A-operands of a 32-key block (4 k-steps of 16 dims)
+struct VFrags { bf16x8 a[2][2]; };  // V^T A-operands [16-key group][32-dim block]
+
 __device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32, 64); }
 
+// Exchange between the two half-waves: returns max(x, x of the lane 32 away).
+__device__ __forceinline__ float xhalf_max(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ __forceinline__ KFrags load_k(const uint8_t *blk, int lane)
+{
+    KFrags f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) f.a[s] = *(const bf16x8 *)(blk + (s * 64 + lane) * 16);
+    return f;
+}
+
+__device__ __forceinline__ VFrags load_v(const uint8_t *blk, int lane)
+{
+    VFrags f;
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+            f.a[g][db] = *(const bf16x8 *)(blk + 4096 + ((g * 2 + db) * 64 + lane) * 16);
+    return f;
+}
+
+// S^T[qb] = K_blk q_qb^T for both query blocks
+__device__ __forceinline__ void qk_block(const QState &st, const KFrags &k, f32x16 (&S)[2])
+{
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) S[qb][r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+            S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k.a[s], st.qf[qb][s], S[qb], 0, 0, 0);
+}
+
+// O^T[db][qb] += V^T_{g,db} P^T
+__device__ __forceinline__ void pv_block(QState &st, const VFrags &v, const bf16x8 (&P)[2][2])
+{
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+                st.O[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v.a[g][db], P[qb][g], st.O[db][qb], 0, 0, 0);
+}
+
+// keys with index >= k_hi are excluded (last blocks of a range only)
+__device__ __forceinline__ void mask_block(f32x16 (&S)[2], int hf, int blk_lo, int k_hi)
+{
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int kidx = blk_lo + 8 * (r >> 2) + 4 * hf + (r & 3);
+        if (kidx >= k_hi) {
+            S[0][r] = -INFINITY;
+            S[1][r] = -INFINITY;
+        }
+    }
+}
+
+// p = exp2(S*scale - sub) rounded to bf16 in B-operand order (P[g] holds the keys of 16-key
+// group g); returns the sum of the ROUNDED values (v_dot2 with ones): the numbers P V multiplies.
+template <bool AFFINE>
+__device__ __forceinline__ float exp_pack(const f32x16 &S, float scale, float sub, bf16x8 (&P)[2])
+{
+    bf16x2 ones;
+    ones[0] = (__bf16)1.f;
+    ones[1] = (__bf16)1.f;
+    float sum = 0.f;
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            bf16x2 pp;
+            pp[0] = (__bf16)__builtin_amdgcn_exp2f(AFFINE ? fmaf(S[8 * g + e], scale, -sub) : S[8 * g + e]);
+            pp[1] = (__bf16)__builtin_amdgcn_exp2f(AFFINE ? fmaf(S[8 * g + e + 1], scale, -sub) : S[8 * g + e + 1]);
+            P[g][e] = pp[0];
+            P[g][e + 1] = pp[1];
+            sum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, sum, false);
+        }
+    return sum;
+}
+
+// FAST softmax of one block: p = exp2(t)
+__device__ __forceinline__ void softmax_fast(QState &st, const f32x16 (&S)[2], bf16x8 (&P)[2][2])
+{
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) st.l[qb] += exp_pack<false>(S[qb], 1.f, 0.f, P[qb]);
+}
+
+// SAFE softmax of one block: running maximum in raw logit units, p = exp2((s - m) * c)
+__device__ __forceinline__ void softmax_safe(QState &st, const f32x16 (&S)[2], bf16x8 (&P)[2][2])
+{
+    float mx[2];
+    bool need[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        float v = fmaxf(S[qb][0], S[qb][1]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) v = fmaxf(fmaxf(v, S[qb][r]), S[qb][r + 1]);
+        mx[qb] = xhalf_max(v);  // same in both half-waves
+        need[qb] = (mx[qb] - st.m_ref[qb]) * st.c[qb] > kSafeSlack;
+    }
+    if (__builtin_amdgcn_ballot_w64(need[0] || need[1]) != 0) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const float alpha =
+                need[qb] ? __builtin_amdgcn_exp2f((st.m_ref[qb] - mx[qb]) * st.c[qb]) : 1.f;
+            st.m_ref[qb] = need[qb] ? mx[qb] : st.m_ref[qb];
+            st.l[qb] *= alpha;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) st.O[db][qb][r] *= alpha;
+        }
+    }
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+        st.l[qb] += exp_pack<true>(S[qb], st.c[qb], st.m_ref[qb] * st.c[qb], P[qb]);
+}
+
+// wait until at most `tiles_in_flight` later tiles (NPRE loads each) are still outstanding
+template <int NPRE>
+__device__ __forceinline__ void wait_tiles(int tiles_in_flight)
+{
+    static_assert(NPRE == 2 || NPRE == 4 || NPRE == 8, "vmcnt immediates below");
+    if (tiles_in_flight >= 2) {
+        if (NPRE == 8) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        if (NPRE == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        if (NPRE == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    } else if (tiles_in_flight == 1) {
+        if (NPRE == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        if (NPRE == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if (NPRE == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+}
+
 template <int NW, bool SUMI>
-__global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const KParams p)
+__global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void attn_bf16_kernel(const KParams p)
 {
     constexpr int NT = NW * 64;
-    constexpr int TQ = NW * 64;            // query rows per workgroup
+    constexpr int TQ = NW * 64;  // query rows per workgroup
     constexpr int NPRE = kTileBytes / 16 / NT;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kTileBytes];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kStages * kTileBytes];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
@@ -97,198 +271,209 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const KParams p)
     const uint8_t *kv = p.layer_base + ((size_t)t0 * p.H + (size_t)h * Lpad) * (kDHead * 4) +
                         (size_t)(k_lo / kBlockKeys) * kBlockBytes;
 
-    // ---- per-lane query state: two 32-query blocks per wave ---------------------------------
-    bf16x8 qf[2][4];     // B operands of S^T: Q[query][16s + 8hf + 0..7]
-    float c[2];          // qk_scale * log2(e) / tau_row
-    float m_ref[2];      // reference maximum (raw logit units)
-    float l[2];          // this half-wave's share of the softmax denominator
-    f32x16 O[2][2];      // O^T[d block][query block]
+    // K/V tiles go HBM -> LDS directly (no register staging): every wave copies NPRE slabs of
+    // 1 KiB (64 lanes x 16 B) per tile; the LDS image equals the HBM image.
+    auto issue_tile = [&](int t) __attribute__((always_inline)) {
+        glb_u8 *src = (glb_u8 *)(kv + (size_t)t * kTileBytes + (size_t)tid * 16);
+        lds_u8 *dst = (lds_u8 *)lds + (t % kStages) * kTileBytes + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < NPRE; ++i)
+            __builtin_amdgcn_global_load_lds(src + i * NT * 16, dst + i * NT * 16, 16, 0, 0);
+    };
+    // Make tile t readable: wait for this wave's slabs of tile t (later tiles stay in flight),
+    // barrier (every wave's slabs are in LDS, and every wave is past tile t-2, whose buffer is
+    // the one refilled next), then refill.  The barrier is a bare s_barrier: a fence would drain
+    // the loads that are meant to stay in flight.  Called while tile t-1 is still being computed
+    // (the FAST pass prefetches across the tile boundary), hence t-2.
+    auto sync_tile = [&](int t) __attribute__((always_inline)) {
+        wait_tiles<NPRE>(min(t + kStages - 2, n_tiles) - (t + 1));
+        __builtin_amdgcn_s_barrier();
+        if (t + kStages - 2 < n_tiles && t >= 1) issue_tile(t + kStages - 2);
+    };
+
+    QState st;
     int64_t qrow[2];
-    bool qvalid[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int wq = wave * 64 + qb * 32 + l32;
-        qvalid[qb] = wq < nq;
         qrow[qb] = row0 + min(wq, nq - 1);
-        const __bf16 *qp = p.q + qrow[qb] * p.ld_q + h * kDHead + 8 * hf;
+    }
+
+    // Query operands, and the row's own key/value as the first member of the softmax (SUMI).
+    // FAST: q' = bf16(q*c), own weight exp2(<q',k_own>).  SAFE: q, reference = own logit.
+    auto init_state = [&](auto safe_tag) __attribute__((always_inline)) {
+        constexpr bool SAFE = decltype(safe_tag)::value;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) qf[qb][s] = *(const bf16x8 *)(qp + 16 * s);
-        const int sc = min(max(p.scen[qrow[qb]], 0), p.n_scen - 1);
-        const int bhv = min(max(p.beh[qrow[qb]], 0), p.n_beh - 1);
-        c[qb] = p.scale_log2e / p.tau[sc * p.n_beh + bhv];
-        if (SUMI) {
+        for (int qb = 0; qb < 2; ++qb) {
+            const int sc = min(max(p.scen[qrow[qb]], 0), p.n_scen - 1);
+            const int bhv = min(max(p.beh[qrow[qb]], 0), p.n_beh - 1);
+            const float c = p.scale_log2e / p.tau[sc * p.n_beh + bhv];
+            st.c[qb] = c;
+            const __bf16 *qp = p.q + qrow[qb] * p.ld_q + h * kDHead + 8 * hf;
             const __bf16 *kp = p.k_self + qrow[qb] * p.ld_kv + h * kDHead + 8 * hf;
             float dot = 0.f;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
+                const bf16x8 qq = *(const bf16x8 *)(qp + 16 * s);
                 const bf16x8 kk = *(const bf16x8 *)(kp + 16 * s);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) dot += (float)qf[qb][s][e] * (float)kk[e];
-            }
-            m_ref[qb] = dot + xhalf(dot);
-            l[qb] = hf == 0 ? 1.f : 0.f;
-            const __bf16 *vp = p.v_self + qrow[qb] * p.ld_kv + h * kDHead + 4 * hf;
-#pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const bf16x4 vv = *(const bf16x4 *)(vp + 32 * db + 8 * g);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) O[db][qb][4 * g + e] = (float)vv[e];
+                for (int e = 0; e < 8; ++e) {
+                    const __bf16 qs = SAFE ? qq[e] : (__bf16)((float)qq[e] * c);
+                    st.qf[qb][s][e] = qs;
+                    dot += (float)qs * (float)kk[e];
                 }
-        } else {
-            m_ref[qb] = -INFINITY;
-            l[qb] = 0.f;
-#pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) O[db][qb][r] = 0.f;
-        }
-    }
-
-    // ---- K/V tile pipeline: HBM -> registers -> LDS double buffer ---------------------------
-    uint4 pre[NPRE];
-    if (n_tiles > 0) {
-#pragma unroll
-        for (int i = 0; i < NPRE; ++i) pre[i] = ((const uint4 *)kv)[tid + i * NT];
-#pragma unroll
-        for (int i = 0; i < NPRE; ++i) ((uint4 *)lds)[tid + i * NT] = pre[i];
-    }
-    __syncthreads();
-
-    for (int t = 0; t < n_tiles; ++t) {
-        const uint8_t *cur = lds + (t & 1) * kTileBytes;
-        const bool more = t + 1 < n_tiles;
-        if (more) {
-            const uint4 *src = (const uint4 *)(kv + (size_t)(t + 1) * kTileBytes);
-#pragma unroll
-            for (int i = 0; i < NPRE; ++i) pre[i] = src[tid + i * NT];
-        }
-
-        // S^T[kb][qb] = K_kb Q_qb^T
-        f32x16 S[2][2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) S[kb][qb][r] = 0.f;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const bf16x8 a = *(const bf16x8 *)(cur + kb * kBlockBytes + (s * 64 + lane) * 16);
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-                    S[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][s], S[kb][qb], 0, 0, 0);
             }
-        }
-
-        // keys past the end of the visible range (only possible in the last tile)
-        const int tile_lo = k_lo + t * kTileKeys;
-        if (tile_lo + kTileKeys > k_hi) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kidx = tile_lo + kb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-                    if (kidx >= k_hi) {
-                        S[kb][0][r] = -INFINITY;
-                        S[kb][1][r] = -INFINITY;
-                    }
-                }
-        }
-
-        // row maxima and (rarely) a move of the reference maximum
-        float mx[2];
-        bool need[2];
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            float v = S[0][qb][0];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) v = fmaxf(v, S[kb][qb][r]);
-            v = fmaxf(v, xhalf(v));
-            mx[qb] = v;
-            need[qb] = (v - m_ref[qb]) * c[qb] > kRescaleThreshold;
-        }
-        if (__builtin_amdgcn_ballot_w64(need[0] || need[1]) != 0) {
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                const float alpha = need[qb] ? __builtin_amdgcn_exp2f((m_ref[qb] - mx[qb]) * c[qb]) : 1.f;
-                m_ref[qb] = need[qb] ? mx[qb] : m_ref[qb];
-                l[qb] *= alpha;
+            const float own = dot + xhalf(dot);  // both halves add the same two numbers
+            st.m_ref[qb] = own;
+            float w_own = 0.f;
+            if (SUMI) w_own = SAFE ? 1.f : __builtin_amdgcn_exp2f(own);
+            st.l[qb] = hf == 0 ? w_own : 0.f;
+            if (SUMI) {
+                const __bf16 *vp = p.v_self + qrow[qb] * p.ld_kv + h * kDHead + 4 * hf;
 #pragma unroll
                 for (int db = 0; db < 2; ++db)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) O[db][qb][r] *= alpha;
+                    for (int g = 0; g < 4; ++g) {
+                        const bf16x4 vv = *(const bf16x4 *)(vp + 32 * db + 8 * g);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) st.O[db][qb][4 * g + e] = w_own * (float)vv[e];
+                    }
+            } else {
+#pragma unroll
+                for (int db = 0; db < 2; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) st.O[db][qb][r] = 0.f;
             }
         }
+    };
+    auto prologue = [&]() __attribute__((always_inline)) {
+        // tiles 0 .. kStages-2 in flight; sync_tile(t >= 1) adds tile t + kStages - 2
+        for (int t = 0; t < kStages - 1 && t < n_tiles; ++t) issue_tile(t);
+    };
 
-        // probabilities, rounded to bf16, in B-operand order: P[qb][kb][g] holds keys of group g
-        bf16x8 P[2][2][2];
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const float mc = m_ref[qb] * c[qb];
-            float sum = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int g = 0; g < 2; ++g)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float pv = __builtin_amdgcn_exp2f(fmaf(S[kb][qb][8 * g + e], c[qb], -mc));
-                        const __bf16 pb = (__bf16)pv;
-                        P[qb][kb][g][e] = pb;
-                        sum += (float)pb;
-                    }
-            l[qb] += sum;
+    // ---- FAST pass, software pipelined over 32-key blocks -----------------------------------
+    prologue();
+    init_state(std::false_type{});
+    if (n_tiles > 0) {
+        f32x16 S0[2], S1[2];
+        bf16x8 P[2][2];
+        wait_tiles<NPRE>(min(kStages - 1, n_tiles) - 1);
+        __builtin_amdgcn_s_barrier();
+        {
+            const KFrags k0 = load_k(lds, lane);
+            qk_block(st, k0, S0);
         }
-
-        // O^T[db][qb] += V^T_{kb,g,db} P^T
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int g = 0; g < 2; ++g)
-#pragma unroll
-                for (int db = 0; db < 2; ++db) {
-                    const bf16x8 a = *(const bf16x8 *)(cur + kb * kBlockBytes + 4096 +
-                                                       ((g * 2 + db) * 64 + lane) * 16);
-#pragma unroll
-                    for (int qb = 0; qb < 2; ++qb)
-                        O[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, P[qb][kb][g], O[db][qb], 0, 0, 0);
-                }
-
-        if (more) {
-            uint4 *dst = (uint4 *)(lds + ((t + 1) & 1) * kTileBytes);
-#pragma unroll
-            for (int i = 0; i < NPRE; ++i) dst[tid + i * NT] = pre[i];
+        for (int t = 0; t + 1 < n_tiles; ++t) {  // every tile but the last: 64 unmasked keys
+            const uint8_t *cur = lds + (t % kStages) * kTileBytes;
+            const uint8_t *nxt = lds + ((t + 1) % kStages) * kTileBytes;
+            {   // block 0 of tile t: its logits are in S0; start block 1's logits
+                const KFrags k1 = load_k(cur + kBlockBytes, lane);
+                const VFrags v0 = load_v(cur, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                qk_block(st, k1, S1);
+                softmax_fast(st, S0, P);
+                pv_block(st, v0, P);
+            }
+            sync_tile(t + 1);
+            {   // block 1 of tile t; start block 0 of tile t+1
+                const KFrags k0 = load_k(nxt, lane);
+                const VFrags v1 = load_v(cur + kBlockBytes, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                qk_block(st, k0, S0);
+                softmax_fast(st, S1, P);
+                pv_block(st, v1, P);
+            }
         }
-        __syncthreads();
+        {   // last tile: 1..64 keys, S0 holds its first block
+            const int t = n_tiles - 1;
+            const uint8_t *cur = lds + (t % kStages) * kTileBytes;
+            const int tile_lo = k_lo + t * kTileKeys;
+            const bool two = tile_lo + kBlockKeys < k_hi;
+            if (two) {
+                const KFrags k1 = load_k(cur + kBlockBytes, lane);
+                qk_block(st, k1, S1);
+            }
+            if (tile_lo + kBlockKeys > k_hi) mask_block(S0, hf, tile_lo, k_hi);
+            {
+                const VFrags v0 = load_v(cur, lane);
+                softmax_fast(st, S0, P);
+                pv_block(st, v0, P);
+            }
+            if (two) {
+                if (tile_lo + kTileKeys > k_hi) mask_block(S1, hf, tile_lo + kBlockKeys, k_hi);
+                const VFrags v1 = load_v(cur + kBlockBytes, lane);
+                softmax_fast(st, S1, P);
+                pv_block(st, v1, P);
+            }
+        }
     }
 
-    // ---- normalise and store: lane holds O^T[32db + 8g + 4hf + 0..3][query] -----------------
+    // ---- SAFE pass (rare): whole workgroup redoes its rows with a running maximum -----------
+    float lt[2];
+    bool bad = false;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const float lt = l[qb] + xhalf(l[qb]);
-        const float inv = 1.f / lt;
-        const int wq = wave * 64 + qb * 32 + l32;
-        __bf16 *op = p.o + (row0 + wq) * p.ld_o + h * kDHead + 4 * hf;
-        if (qvalid[qb]) {
+        lt[qb] = st.l[qb] + xhalf(st.l[qb]);
+        bad |= !(lt[qb] > kDenomLo && lt[qb] < kDenomHi);
+    }
+    if (__syncthreads_or(bad)) {  // also orders the reuse of the LDS ring
+        prologue();
+        init_state(std::true_type{});
+        for (int t = 0; t < n_tiles; ++t) {
+            wait_tiles<NPRE>(min(t + kStages - 1, n_tiles) - (t + 1));
+            __builtin_amdgcn_s_barrier();
+            if (t + kStages - 1 < n_tiles) issue_tile(t + kStages - 1);
+            const uint8_t *cur = lds + (t % kStages) * kTileBytes;
+            const int tile_lo = k_lo + t * kTileKeys;
 #pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 ov;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(O[db][qb][4 * g + e] * inv);
-                    *(bf16x4 *)(op + 32 * db + 8 * g) = ov;
+            for (int blk = 0; blk < 2; ++blk) {
+                const int blk_lo = tile_lo + blk * kBlockKeys;
+                if (blk_lo < k_hi) {
+                    f32x16 S[2];
+                    bf16x8 P[2][2];
+                    const KFrags kf = load_k(cur + blk * kBlockBytes, lane);
+                    qk_block(st, kf, S);
+                    if (blk_lo + kBlockKeys > k_hi) mask_block(S, hf, blk_lo, k_hi);
+                    softmax_safe(st, S, P);
+                    const VFrags vf = load_v(cur + blk * kBlockBytes, lane);
+                    pv_block(st, vf, P);
                 }
-        } else if (!SUMI && q0 + wq < Lpad) {
-            const bf16x4 z = {(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+            }
+        }
 #pragma unroll
-            for (int db = 0; db < 2; ++db)
+        for (int qb = 0; qb < 2; ++qb) lt[qb] = st.l[qb] + xhalf(st.l[qb]);
+    }
+
+    // ---- normalise and store ----------------------------------------------------------------
+    // A lane holds O^T[32db + 8g + 4hf + 0..3][query]: 8-byte pieces of 32 different rows.  Each
+    // wave turns its 32 x 64 block around in its own corner of the (now idle) LDS ring so that
+    // the global stores are whole 128-byte rows, 16 bytes per lane.
+    __syncthreads();  // every wave is done reading K/V tiles
+    constexpr int kRowPitch = 144;  // 128 B of a row + 16 B pad, keeps 16-byte alignment
+    uint8_t *tr = lds + wave * (32 * kRowPitch);
 #pragma unroll
-                for (int g = 0; g < 4; ++g) *(bf16x4 *)(op + 32 * db + 8 * g) = z;
+    for (int qb = 0; qb < 2; ++qb) {
+        const float inv = 1.f / lt[qb];
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 ov;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(st.O[db][qb][4 * g + e] * inv);
+                *(bf16x4 *)(tr + l32 * kRowPitch + (32 * db + 8 * g + 4 * hf) * 2) = ov;
+            }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int id = i * 64 + lane, r = id >> 3, cc = id & 7;
+            const int wq = wave * 64 + qb * 32 + r;
+            uint4 val = *(const uint4 *)(tr + r * kRowPitch + cc * 16);
+            __bf16 *op = p.o + (row0 + wq) * p.ld_o + h * kDHead + cc * 8;
+            if (wq < nq) {
+                *(uint4 *)op = val;
+            } else if (!SUMI && q0 + wq < Lpad) {
+                *(uint4 *)op = uint4{0, 0, 0, 0};
+            }
         }
     }
 }
@@ -334,15 +519,37 @@ hipError_t launch(const AttnArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+// Query-tile width: NW waves x 64 queries per workgroup.  Wider tiles re-read a head's K/V from
+// L2 fewer times; narrower ones give more workgroups when there are few queries per head.
+// CLIMBER_ATTN_NW (2, 4 or 8) overrides the choice, for tuning.
+int forced_nw()
+{
+    static const int v = [] {
+        const char *e = getenv("CLIMBER_ATTN_NW");
+        return e ? atoi(e) : 0;
+    }();
+    return v;
+}
+
 }  // namespace
 
 hipError_t launch_attn_sumi_bf16(const AttnArgs &a, hipStream_t s)
 {
+    int nw = forced_nw();
+    if (nw != 2 && nw != 4 && nw != 8) nw = a.max_rows_per_user > 128 ? 4 : 2;
+    if (nw == 8) return launch<8, true>(a, s);
+    if (nw == 4) return launch<4, true>(a, s);
     return launch<2, true>(a, s);
 }
 
 hipError_t launch_attn_hist_bf16(const AttnArgs &a, hipStream_t s)
 {
+    // a query tile must lie inside one subsequence
+    int nw = forced_nw();
+    if (nw != 2 && nw != 4 && nw != 8) nw = 2;
+    while (nw > 2 && a.sub_len % (nw * 64) != 0) nw >>= 1;
+    if (nw == 8) return launch<8, false>(a, s);
+    if (nw == 4) return launch<4, false>(a, s);
     return launch<2, false>(a, s);
 }
 

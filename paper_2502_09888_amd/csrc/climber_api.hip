@@ -132,6 +132,8 @@ int attn_history_strided(const climber_config *cfg, const float *tau_layer, cons
     if (!o) return CLIMBER_OK;
     AttnArgs a = base_args(cfg, cache, layer, tau_layer);
     a.q = q;
+    a.k_self = k;  // a history row's own key seeds its softmax reference
+    a.v_self = v;
     a.ld_q = ld;
     a.ld_kv = ld;
     a.scen = scen;
