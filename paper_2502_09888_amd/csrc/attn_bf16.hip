@@ -44,7 +44,6 @@ typedef const __attribute__((address_space(1))) uint8_t glb_u8;
 
 constexpr int kTileKeys = 64;                // keys per LDS tile = 2 cache blocks
 constexpr int kTileBytes = 2 * kBlockBytes;  // 16 KiB
-constexpr int kStages = 4;                   // LDS ring: 3 tiles in flight ahead of the computed one
 constexpr float kSafeSlack = 8.0f;           // SAFE: exp2-domain slack before the row maximum moves
 constexpr float kDenomHi = 1.0e12f;          // FAST is accepted iff kDenomLo < denominator < kDenomHi
 constexpr float kDenomLo = 1.0e-12f;
@@ -58,6 +57,8 @@ struct KParams {
     __bf16 *o;
     int64_t ld_q, ld_kv, ld_o;
     int B, H, n_scen, n_beh, sub_len, n_qtiles;
+    int uni_len, uni_pad;  // >= 0: every user has this valid / padded history length
+    int uni_cand;          // >= 0: every user has this many candidates (SUMI)
     float scale_log2e;
 };
 
@@ -220,9 +221,10 @@ __device__ __forceinline__ void wait_tiles(int tiles_in_flight)
     }
 }
 
-template <int NW, bool SUMI>
-__global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void attn_bf16_kernel(const KParams p)
+template <int NW, bool SUMI, int kStages>
+__global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 {
+    static_assert(kStages >= 3, "tile t+1 is read while tile t is computed and one more is in flight");
     constexpr int NT = NW * 64;
     constexpr int TQ = NW * 64;  // query rows per workgroup
     constexpr int NPRE = kTileBytes / 16 / NT;
@@ -239,14 +241,33 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void attn_bf16_kernel(con
     const int qt = j % p.n_qtiles;
     const int bh = (j / p.n_qtiles) * 8 + xcd;
     if (bh >= p.B * p.H) return;
-    const int b = p.order[bh / p.H], h = bh % p.H;
-    const int Lb = p.hist_len[b], t0 = p.tok_off[b], Lpad = p.tok_off[b + 1] - t0;
+    // Uniform batches (the host knows): user geometry comes from kernel arguments, which saves
+    // two dependent trips to memory at the start of every workgroup.
+    const int h = bh % p.H;
+    int b = bh / p.H, Lb, t0, Lpad;
+    if (p.uni_len >= 0) {
+        Lb = p.uni_len;
+        Lpad = p.uni_pad;
+        t0 = b * Lpad;
+    } else {
+        b = p.order[b];
+        Lb = p.hist_len[b];
+        t0 = p.tok_off[b];
+        Lpad = p.tok_off[b + 1] - t0;
+    }
 
     const int q0 = qt * TQ;
     int64_t row0;
     int nq, k_lo, k_hi;
     if (SUMI) {
-        const int c0 = p.cand_off[b], Mb = p.cand_off[b + 1] - c0;
+        int c0, Mb;
+        if (p.uni_cand >= 0) {
+            Mb = p.uni_cand;
+            c0 = b * Mb;
+        } else {
+            c0 = p.cand_off[b];
+            Mb = p.cand_off[b + 1] - c0;
+        }
         if (q0 >= Mb) return;
         row0 = (int64_t)c0 + q0;
         nq = min(TQ, Mb - q0);
@@ -291,6 +312,15 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void attn_bf16_kernel(con
         if (t + kStages - 2 < n_tiles && t >= 1) issue_tile(t + kStages - 2);
     };
 
+    // The temperature table is staged in the last ring buffer (first refilled during tile 0, i.e.
+    // after the lookups) so that the per-row lookup is not a second dependent trip to memory.
+    constexpr int kTauLds = kTileBytes / 4;
+    float *tau_lds = (float *)(lds + (kStages - 1) * kTileBytes);
+    const int n_tau = p.n_scen * p.n_beh;
+    const bool tau_in_lds = n_tau <= kTauLds;
+    if (tau_in_lds)
+        for (int i = tid; i < n_tau; i += NT) tau_lds[i] = p.tau[i];
+
     QState st;
     int64_t qrow[2];
 #pragma unroll
@@ -301,14 +331,23 @@ __global__ __launch_bounds__(NW * 64, NW >= 4 ? 2 : 1) void attn_bf16_kernel(con
 
     // Query operands, and the row's own key/value as the first member of the softmax (SUMI).
     // FAST: q' = bf16(q*c), own weight exp2(<q',k_own>).  SAFE: q, reference = own logit.
+    int tau_idx[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int sc = min(max(p.scen[qrow[qb]], 0), p.n_scen - 1);
+        const int bhv = min(max(p.beh[qrow[qb]], 0), p.n_beh - 1);
+        tau_idx[qb] = sc * p.n_beh + bhv;
+    }
+    __syncthreads();  // tau_lds is written
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+        st.c[qb] = p.scale_log2e / (tau_in_lds ? tau_lds[tau_idx[qb]] : p.tau[tau_idx[qb]]);
+
     auto init_state = [&](auto safe_tag) __attribute__((always_inline)) {
         constexpr bool SAFE = decltype(safe_tag)::value;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            const int sc = min(max(p.scen[qrow[qb]], 0), p.n_scen - 1);
-            const int bhv = min(max(p.beh[qrow[qb]], 0), p.n_beh - 1);
-            const float c = p.scale_log2e / p.tau[sc * p.n_beh + bhv];
-            st.c[qb] = c;
+            const float c = st.c[qb];
             const __bf16 *qp = p.q + qrow[qb] * p.ld_q + h * kDHead + 8 * hf;
             const __bf16 *kp = p.k_self + qrow[qb] * p.ld_kv + h * kDHead + 8 * hf;
             float dot = 0.f;
@@ -503,11 +542,14 @@ KParams make_params(const AttnArgs &a, int n_qtiles)
     p.sub_len = a.sub_len;
     p.n_qtiles = n_qtiles;
     p.scale_log2e = a.qk_scale * 1.4426950408889634f;
+    p.uni_len = a.uni_len;
+    p.uni_pad = a.uni_pad;
+    p.uni_cand = a.uni_cand;
     return p;
 }
 
-template <int NW, bool SUMI>
-hipError_t launch(const AttnArgs &a, hipStream_t s)
+template <int NW, bool SUMI, int kStages>
+hipError_t launch_st(const AttnArgs &a, hipStream_t s)
 {
     constexpr int TQ = NW * 64;
     const int n_qtiles = (a.max_rows_per_user + TQ - 1) / TQ;
@@ -515,8 +557,25 @@ hipError_t launch(const AttnArgs &a, hipStream_t s)
     const int64_t grid = (int64_t)8 * n_qtiles * groups;
     if (grid <= 0 || grid > 0x7fffffff) return hipErrorInvalidValue;
     const KParams p = make_params(a, n_qtiles);
-    hipLaunchKernelGGL((attn_bf16_kernel<NW, SUMI>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<NW, SUMI, kStages>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
     return hipGetLastError();
+}
+
+int forced_stages()
+{
+    static const int v = [] {
+        const char *e = getenv("CLIMBER_ATTN_STAGES");
+        return e ? atoi(e) : 0;
+    }();
+    return v;
+}
+
+template <int NW, bool SUMI>
+hipError_t launch(const AttnArgs &a, hipStream_t s)
+{
+    const int st = forced_stages();
+    if (st == 3) return launch_st<NW, SUMI, 3>(a, s);
+    return launch_st<NW, SUMI, 4>(a, s);
 }
 
 // Query-tile width: NW waves x 64 queries per workgroup.  Wider tiles re-read a head's K/V from

@@ -21,6 +21,7 @@ struct climber_kv_cache {
     uint8_t *dev;
     size_t bytes, header_bytes, layer_bytes;
     int32_t max_pad, max_len;
+    int32_t uni_len, uni_pad;  // >= 0 when all users share one valid / padded length
     int64_t rows;
 };
 
@@ -99,6 +100,9 @@ AttnArgs base_args(const climber_config *cfg, const climber_kv_cache *cache, int
     a.causal = (cfg->flags & CLIMBER_HIST_CAUSAL) ? 1 : 0;
     a.qk_scale = cfg->qk_scale;
     a.max_hist_len = cache->max_len;
+    a.uni_len = cache->uni_len;
+    a.uni_pad = cache->uni_pad;
+    a.uni_cand = -1;
     return a;
 }
 
@@ -166,6 +170,8 @@ int attn_sumi_strided(const climber_config *cfg, const float *tau_layer,
     a.ld_o = ld_o;
     a.max_rows_per_user = m_max;
     a.total_q_rows = m_total;
+    // m_max >= every user's count and the counts sum to m_total: equality means all are m_max
+    if ((int64_t)m_max * cache->B == (int64_t)m_total) a.uni_cand = m_max;
     if (cfg->dtype == CLIMBER_BF16) return rt(launch_attn_sumi_bf16(a, s));
     return rt(launch_attn_f32(a, true, cache->rows, s));
 }
@@ -249,6 +255,11 @@ int climber_kv_cache_create(const climber_config *cfg, int32_t B, const int32_t 
     k->layer_bytes = 2 * (size_t)rows * cfg->d_model * elem_size(cfg->dtype);
     k->max_pad = max_pad;
     k->max_len = max_len;
+    bool uni = true;
+    for (int b = 1; b < B; ++b)
+        uni = uni && hist_len[b] == hist_len[0] && hist_len_padded[b] == hist_len_padded[0];
+    k->uni_len = uni ? hist_len[0] : -1;
+    k->uni_pad = uni ? hist_len_padded[0] : -1;
     k->rows = rows;
 
     std::vector<int32_t> hd;

@@ -41,6 +41,8 @@ struct AttnArgs {
     int max_rows_per_user;           // SUMI: m_max; history: longest padded history
     int64_t total_q_rows;            // SUMI: m_total; history: padded rows of the batch
     int max_hist_len;                // longest valid history of the batch
+    int uni_len, uni_pad;            // >= 0: all users share this valid / padded history length
+    int uni_cand;                    // >= 0: all users have this many candidates (SUMI)
     float qk_scale;
 };
 
