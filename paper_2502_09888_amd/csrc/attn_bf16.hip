@@ -62,13 +62,14 @@ struct KParams {
     float scale_log2e;
 };
 
-// Per-wave softmax state for 64 queries (two 32-query blocks).
+// Per-wave softmax state for QB blocks of 32 queries.
+template <int QB>
 struct QState {
-    bf16x8 qf[2][4];  // B operands of S^T: FAST q' = bf16(q*c), SAFE q; [query][16s + 8hf + 0..7]
-    float c[2];       // qk_scale * log2(e) / tau_row                       (SAFE)
-    float m_ref[2];   // running reference maximum, raw logit units         (SAFE)
-    float l[2];       // this half-wave's share of the softmax denominator
-    f32x16 O[2][2];   // O^T[d block][query block]
+    bf16x8 qf[QB][4];  // B operands of S^T: FAST q' = bf16(q*c), SAFE q; [query][16s + 8hf + 0..7]
+    float c[QB];      // qk_scale * log2(e) / tau_row                       (SAFE)
+    float m_ref[QB];  // running reference maximum, raw logit units         (SAFE)
+    float l[QB];      // this half-wave's share of the softmax denominator
+    f32x16 O[2][QB];  // O^T[d block][query block]
 };
 
 struct KFrags { bf16x8 a[4]; };  // K A-operands of a 32-key block (4 k-steps of 16 dims)
@@ -104,40 +105,43 @@ __device__ __forceinline__ VFrags load_v(const uint8_t *blk, int lane)
 }
 
 // S^T[qb] = K_blk q_qb^T for both query blocks
-__device__ __forceinline__ void qk_block(const QState &st, const KFrags &k, f32x16 (&S)[2])
+template <int QB>
+__device__ __forceinline__ void qk_block(const QState<QB> &st, const KFrags &k, f32x16 (&S)[QB])
 {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) S[qb][r] = 0.f;
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
             S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k.a[s], st.qf[qb][s], S[qb], 0, 0, 0);
 }
 
 // O^T[db][qb] += V^T_{g,db} P^T
-__device__ __forceinline__ void pv_block(QState &st, const VFrags &v, const bf16x8 (&P)[2][2])
+template <int QB>
+__device__ __forceinline__ void pv_block(QState<QB> &st, const VFrags &v, const bf16x8 (&P)[QB][2])
 {
 #pragma unroll
     for (int g = 0; g < 2; ++g)
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int qb = 0; qb < QB; ++qb)
                 st.O[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v.a[g][db], P[qb][g], st.O[db][qb], 0, 0, 0);
 }
 
 // keys with index >= k_hi are excluded (last blocks of a range only)
-__device__ __forceinline__ void mask_block(f32x16 (&S)[2], int hf, int blk_lo, int k_hi)
+template <int QB>
+__device__ __forceinline__ void mask_block(f32x16 (&S)[QB], int hf, int blk_lo, int k_hi)
 {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int kidx = blk_lo + 8 * (r >> 2) + 4 * hf + (r & 3);
         if (kidx >= k_hi) {
-            S[0][r] = -INFINITY;
-            S[1][r] = -INFINITY;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) S[qb][r] = -INFINITY;
         }
     }
 }
@@ -166,28 +170,32 @@ __device__ __forceinline__ float exp_pack(const f32x16 &S, float scale, float su
 }
 
 // FAST softmax of one block: p = exp2(t)
-__device__ __forceinline__ void softmax_fast(QState &st, const f32x16 (&S)[2], bf16x8 (&P)[2][2])
+template <int QB>
+__device__ __forceinline__ void softmax_fast(QState<QB> &st, const f32x16 (&S)[QB], bf16x8 (&P)[QB][2])
 {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) st.l[qb] += exp_pack<false>(S[qb], 1.f, 0.f, P[qb]);
+    for (int qb = 0; qb < QB; ++qb) st.l[qb] += exp_pack<false>(S[qb], 1.f, 0.f, P[qb]);
 }
 
 // SAFE softmax of one block: running maximum in raw logit units, p = exp2((s - m) * c)
-__device__ __forceinline__ void softmax_safe(QState &st, const f32x16 (&S)[2], bf16x8 (&P)[2][2])
+template <int QB>
+__device__ __forceinline__ void softmax_safe(QState<QB> &st, const f32x16 (&S)[QB], bf16x8 (&P)[QB][2])
 {
-    float mx[2];
-    bool need[2];
+    float mx[QB];
+    bool need[QB];
+    bool any = false;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         float v = fmaxf(S[qb][0], S[qb][1]);
 #pragma unroll
         for (int r = 2; r < 16; r += 2) v = fmaxf(fmaxf(v, S[qb][r]), S[qb][r + 1]);
         mx[qb] = xhalf_max(v);  // same in both half-waves
         need[qb] = (mx[qb] - st.m_ref[qb]) * st.c[qb] > kSafeSlack;
+        any |= need[qb];
     }
-    if (__builtin_amdgcn_ballot_w64(need[0] || need[1]) != 0) {
+    if (__builtin_amdgcn_ballot_w64(any) != 0) {
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
             const float alpha =
                 need[qb] ? __builtin_amdgcn_exp2f((st.m_ref[qb] - mx[qb]) * st.c[qb]) : 1.f;
             st.m_ref[qb] = need[qb] ? mx[qb] : st.m_ref[qb];
@@ -199,7 +207,7 @@ __device__ __forceinline__ void softmax_safe(QState &st, const f32x16 (&S)[2], b
         }
     }
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
         st.l[qb] += exp_pack<true>(S[qb], st.c[qb], st.m_ref[qb] * st.c[qb], P[qb]);
 }
 
@@ -221,12 +229,13 @@ __device__ __forceinline__ void wait_tiles(int tiles_in_flight)
     }
 }
 
-template <int NW, bool SUMI, int kStages>
+template <int NW, int QB, bool SUMI, int kStages>
 __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 {
     static_assert(kStages >= 3, "tile t+1 is read while tile t is computed and one more is in flight");
     constexpr int NT = NW * 64;
-    constexpr int TQ = NW * 64;  // query rows per workgroup
+    constexpr int WQ = 32 * QB;  // query rows per wave
+    constexpr int TQ = NW * WQ;  // query rows per workgroup
     constexpr int NPRE = kTileBytes / 16 / NT;
     __shared__ __attribute__((aligned(16))) uint8_t lds[kStages * kTileBytes];
 
@@ -321,32 +330,32 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     if (tau_in_lds)
         for (int i = tid; i < n_tau; i += NT) tau_lds[i] = p.tau[i];
 
-    QState st;
-    int64_t qrow[2];
+    QState<QB> st;
+    int64_t qrow[QB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const int wq = wave * 64 + qb * 32 + l32;
+    for (int qb = 0; qb < QB; ++qb) {
+        const int wq = wave * WQ + qb * 32 + l32;
         qrow[qb] = row0 + min(wq, nq - 1);
     }
 
     // Query operands, and the row's own key/value as the first member of the softmax (SUMI).
     // FAST: q' = bf16(q*c), own weight exp2(<q',k_own>).  SAFE: q, reference = own logit.
-    int tau_idx[2];
+    int tau_idx[QB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         const int sc = min(max(p.scen[qrow[qb]], 0), p.n_scen - 1);
         const int bhv = min(max(p.beh[qrow[qb]], 0), p.n_beh - 1);
         tau_idx[qb] = sc * p.n_beh + bhv;
     }
     __syncthreads();  // tau_lds is written
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
         st.c[qb] = p.scale_log2e / (tau_in_lds ? tau_lds[tau_idx[qb]] : p.tau[tau_idx[qb]]);
 
     auto init_state = [&](auto safe_tag) __attribute__((always_inline)) {
         constexpr bool SAFE = decltype(safe_tag)::value;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
             const float c = st.c[qb];
             const __bf16 *qp = p.q + qrow[qb] * p.ld_q + h * kDHead + 8 * hf;
             const __bf16 *kp = p.k_self + qrow[qb] * p.ld_kv + h * kDHead + 8 * hf;
@@ -394,8 +403,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     prologue();
     init_state(std::false_type{});
     if (n_tiles > 0) {
-        f32x16 S0[2], S1[2];
-        bf16x8 P[2][2];
+        f32x16 S0[QB], S1[QB];
+        bf16x8 P[QB][2];
         wait_tiles<NPRE>(min(kStages - 1, n_tiles) - 1);
         __builtin_amdgcn_s_barrier();
         {
@@ -448,10 +457,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     }
 
     // ---- SAFE pass (rare): whole workgroup redoes its rows with a running maximum -----------
-    float lt[2];
+    float lt[QB];
     bool bad = false;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         lt[qb] = st.l[qb] + xhalf(st.l[qb]);
         bad |= !(lt[qb] > kDenomLo && lt[qb] < kDenomHi);
     }
@@ -468,8 +477,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             for (int blk = 0; blk < 2; ++blk) {
                 const int blk_lo = tile_lo + blk * kBlockKeys;
                 if (blk_lo < k_hi) {
-                    f32x16 S[2];
-                    bf16x8 P[2][2];
+                    f32x16 S[QB];
+                    bf16x8 P[QB][2];
                     const KFrags kf = load_k(cur + blk * kBlockBytes, lane);
                     qk_block(st, kf, S);
                     if (blk_lo + kBlockKeys > k_hi) mask_block(S, hf, blk_lo, k_hi);
@@ -480,7 +489,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             }
         }
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) lt[qb] = st.l[qb] + xhalf(st.l[qb]);
+        for (int qb = 0; qb < QB; ++qb) lt[qb] = st.l[qb] + xhalf(st.l[qb]);
     }
 
     // ---- normalise and store ----------------------------------------------------------------
@@ -491,7 +500,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     constexpr int kRowPitch = 144;  // 128 B of a row + 16 B pad, keeps 16-byte alignment
     uint8_t *tr = lds + wave * (32 * kRowPitch);
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         const float inv = 1.f / lt[qb];
 #pragma unroll
         for (int db = 0; db < 2; ++db)
@@ -505,7 +514,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int id = i * 64 + lane, r = id >> 3, cc = id & 7;
-            const int wq = wave * 64 + qb * 32 + r;
+            const int wq = wave * WQ + qb * 32 + r;
             uint4 val = *(const uint4 *)(tr + r * kRowPitch + cc * 16);
             __bf16 *op = p.o + (row0 + wq) * p.ld_o + h * kDHead + cc * 8;
             if (wq < nq) {
@@ -548,68 +557,60 @@ KParams make_params(const AttnArgs &a, int n_qtiles)
     return p;
 }
 
-template <int NW, bool SUMI, int kStages>
-hipError_t launch_st(const AttnArgs &a, hipStream_t s)
+template <int NW, int QB, bool SUMI>
+hipError_t launch(const AttnArgs &a, hipStream_t s)
 {
-    constexpr int TQ = NW * 64;
+    constexpr int TQ = NW * 32 * QB;
     const int n_qtiles = (a.max_rows_per_user + TQ - 1) / TQ;
     const int groups = (a.cache.B * a.H + 7) / 8;
     const int64_t grid = (int64_t)8 * n_qtiles * groups;
     if (grid <= 0 || grid > 0x7fffffff) return hipErrorInvalidValue;
     const KParams p = make_params(a, n_qtiles);
-    hipLaunchKernelGGL((attn_bf16_kernel<NW, SUMI, kStages>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<NW, QB, SUMI, 4>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
     return hipGetLastError();
 }
 
-int forced_stages()
+// Query-tile shape: NW waves x QB blocks of 32 queries per workgroup.  Wide tiles re-read a head's
+// K/V from L2 fewer times and reuse every LDS fragment for two MFMAs; narrow ones keep two waves
+// per SIMD busy when a head has few queries.  CLIMBER_ATTN_TILE=<NW><QB> (e.g. 42) overrides the
+// choice, for tuning.
+int forced_tile()
 {
     static const int v = [] {
-        const char *e = getenv("CLIMBER_ATTN_STAGES");
+        const char *e = getenv("CLIMBER_ATTN_TILE");
         return e ? atoi(e) : 0;
     }();
     return v;
 }
 
-template <int NW, bool SUMI>
-hipError_t launch(const AttnArgs &a, hipStream_t s)
+template <bool SUMI>
+hipError_t dispatch(const AttnArgs &a, int tile, hipStream_t s)
 {
-    const int st = forced_stages();
-    if (st == 3) return launch_st<NW, SUMI, 3>(a, s);
-    return launch_st<NW, SUMI, 4>(a, s);
-}
-
-// Query-tile width: NW waves x 64 queries per workgroup.  Wider tiles re-read a head's K/V from
-// L2 fewer times; narrower ones give more workgroups when there are few queries per head.
-// CLIMBER_ATTN_NW (2, 4 or 8) overrides the choice, for tuning.
-int forced_nw()
-{
-    static const int v = [] {
-        const char *e = getenv("CLIMBER_ATTN_NW");
-        return e ? atoi(e) : 0;
-    }();
-    return v;
+    switch (tile) {
+    case 22: return launch<2, 2, SUMI>(a, s);
+    case 41: return launch<4, 1, SUMI>(a, s);
+    case 82: return launch<8, 2, SUMI>(a, s);
+    default: return launch<4, 2, SUMI>(a, s);
+    }
 }
 
 }  // namespace
 
 hipError_t launch_attn_sumi_bf16(const AttnArgs &a, hipStream_t s)
 {
-    int nw = forced_nw();
-    if (nw != 2 && nw != 4 && nw != 8) nw = a.max_rows_per_user > 128 ? 4 : 2;
-    if (nw == 8) return launch<8, true>(a, s);
-    if (nw == 4) return launch<4, true>(a, s);
-    return launch<2, true>(a, s);
+    int tile = forced_tile();
+    if (tile == 0) tile = a.max_rows_per_user > 128 ? 42 : 41;
+    return dispatch<true>(a, tile, s);
 }
 
 hipError_t launch_attn_hist_bf16(const AttnArgs &a, hipStream_t s)
 {
-    // a query tile must lie inside one subsequence
-    int nw = forced_nw();
-    if (nw != 2 && nw != 4 && nw != 8) nw = 2;
-    while (nw > 2 && a.sub_len % (nw * 64) != 0) nw >>= 1;
-    if (nw == 8) return launch<8, false>(a, s);
-    if (nw == 4) return launch<4, false>(a, s);
-    return launch<2, false>(a, s);
+    // a query tile must lie inside one subsequence (sub_len is 0 or a multiple of 128)
+    int tile = forced_tile();
+    if (tile == 0) tile = 42;
+    const int tq = (tile / 10) * 32 * (tile % 10);
+    if (a.sub_len % tq != 0) tile = 41;
+    return dispatch<false>(a, tile, s);
 }
 
 }  // namespace climber
