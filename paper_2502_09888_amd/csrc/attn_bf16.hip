@@ -229,8 +229,8 @@ __device__ __forceinline__ void wait_tiles(int tiles_in_flight)
     }
 }
 
-template <int NW, int QB, bool SUMI, int kStages>
-__global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
+template <int NW, int QB, bool SUMI, int kStages, bool PIPE, int WPS>
+__global__ __launch_bounds__(NW * 64, WPS) void attn_bf16_kernel(const KParams p)
 {
     static_assert(kStages >= 3, "tile t+1 is read while tile t is computed and one more is in flight");
     constexpr int NT = NW * 64;
@@ -321,15 +321,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         if (t + kStages - 2 < n_tiles && t >= 1) issue_tile(t + kStages - 2);
     };
 
-    // The temperature table is staged in the last ring buffer (first refilled during tile 0, i.e.
-    // after the lookups) so that the per-row lookup is not a second dependent trip to memory.
-    constexpr int kTauLds = kTileBytes / 4;
-    float *tau_lds = (float *)(lds + (kStages - 1) * kTileBytes);
-    const int n_tau = p.n_scen * p.n_beh;
-    const bool tau_in_lds = n_tau <= kTauLds;
-    if (tau_in_lds)
-        for (int i = tid; i < n_tau; i += NT) tau_lds[i] = p.tau[i];
-
     QState<QB> st;
     int64_t qrow[QB];
 #pragma unroll
@@ -338,45 +329,42 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         qrow[qb] = row0 + min(wq, nq - 1);
     }
 
-    // Query operands, and the row's own key/value as the first member of the softmax (SUMI).
-    // FAST: q' = bf16(q*c), own weight exp2(<q',k_own>).  SAFE: q, reference = own logit.
-    int tau_idx[QB];
+    // Query operands.  FAST: q' = bf16(q*c), empty state; the candidate's own key/value joins the
+    // softmax after the history (add_own_fast) so that its rows are not part of what a starting
+    // workgroup has to wait for.  SAFE: q unscaled; the own key/value is the first member and its
+    // logit the first reference.
+    auto load_q_raw = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int sc = min(max(p.scen[qrow[qb]], 0), p.n_scen - 1);
-        const int bhv = min(max(p.beh[qrow[qb]], 0), p.n_beh - 1);
-        tau_idx[qb] = sc * p.n_beh + bhv;
-    }
-    __syncthreads();  // tau_lds is written
+        for (int qb = 0; qb < QB; ++qb) {
+            const __bf16 *qp = p.q + qrow[qb] * p.ld_q + h * kDHead + 8 * hf;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-        st.c[qb] = p.scale_log2e / (tau_in_lds ? tau_lds[tau_idx[qb]] : p.tau[tau_idx[qb]]);
-
+            for (int s = 0; s < 4; ++s) st.qf[qb][s] = *(const bf16x8 *)(qp + 16 * s);
+        }
+    };
     auto init_state = [&](auto safe_tag) __attribute__((always_inline)) {
         constexpr bool SAFE = decltype(safe_tag)::value;
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const float c = st.c[qb];
-            const __bf16 *qp = p.q + qrow[qb] * p.ld_q + h * kDHead + 8 * hf;
             const __bf16 *kp = p.k_self + qrow[qb] * p.ld_kv + h * kDHead + 8 * hf;
             float dot = 0.f;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const bf16x8 qq = *(const bf16x8 *)(qp + 16 * s);
-                const bf16x8 kk = *(const bf16x8 *)(kp + 16 * s);
+                const bf16x8 qq = st.qf[qb][s];  // raw rows from load_q_raw
+                if (SAFE) {
+                    const bf16x8 kk = *(const bf16x8 *)(kp + 16 * s);
+                    st.qf[qb][s] = qq;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const __bf16 qs = SAFE ? qq[e] : (__bf16)((float)qq[e] * c);
-                    st.qf[qb][s][e] = qs;
-                    dot += (float)qs * (float)kk[e];
+                    for (int e = 0; e < 8; ++e) dot += (float)qq[e] * (float)kk[e];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) st.qf[qb][s][e] = (__bf16)((float)qq[e] * c);
                 }
             }
-            const float own = dot + xhalf(dot);  // both halves add the same two numbers
-            st.m_ref[qb] = own;
-            float w_own = 0.f;
-            if (SUMI) w_own = SAFE ? 1.f : __builtin_amdgcn_exp2f(own);
-            st.l[qb] = hf == 0 ? w_own : 0.f;
-            if (SUMI) {
+            st.m_ref[qb] = dot + xhalf(dot);  // both halves add the same two numbers
+            const bool own_first = SAFE && SUMI;
+            st.l[qb] = (own_first && hf == 0) ? 1.f : 0.f;
+            if (own_first) {
                 const __bf16 *vp = p.v_self + qrow[qb] * p.ld_kv + h * kDHead + 4 * hf;
 #pragma unroll
                 for (int db = 0; db < 2; ++db)
@@ -384,7 +372,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                     for (int g = 0; g < 4; ++g) {
                         const bf16x4 vv = *(const bf16x4 *)(vp + 32 * db + 8 * g);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) st.O[db][qb][4 * g + e] = w_own * (float)vv[e];
+                        for (int e = 0; e < 4; ++e) st.O[db][qb][4 * g + e] = (float)vv[e];
                     }
             } else {
 #pragma unroll
@@ -394,15 +382,97 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             }
         }
     };
+    // FAST, SUMI: weight exp2(<q', k_own>) for the candidate's own key, O += weight * v_own.
+    auto add_own_fast = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const __bf16 *kp = p.k_self + qrow[qb] * p.ld_kv + h * kDHead + 8 * hf;
+            const __bf16 *vp = p.v_self + qrow[qb] * p.ld_kv + h * kDHead + 4 * hf;
+            bf16x8 kk[4];
+            bf16x4 vv[2][4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) kk[s] = *(const bf16x8 *)(kp + 16 * s);
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) vv[db][g] = *(const bf16x4 *)(vp + 32 * db + 8 * g);
+            float dot = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot += (float)st.qf[qb][s][e] * (float)kk[s][e];
+            const float w = __builtin_amdgcn_exp2f(dot + xhalf(dot));
+            st.l[qb] += hf == 0 ? w : 0.f;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        st.O[db][qb][4 * g + e] = fmaf(w, (float)vv[db][g][e], st.O[db][qb][4 * g + e]);
+        }
+    };
     auto prologue = [&]() __attribute__((always_inline)) {
         // tiles 0 .. kStages-2 in flight; sync_tile(t >= 1) adds tile t + kStages - 2
         for (int t = 0; t < kStages - 1 && t < n_tiles; ++t) issue_tile(t);
     };
 
     // ---- FAST pass, software pipelined over 32-key blocks -----------------------------------
-    prologue();
+    // Start-up order = what the first MFMA needs first: tile 0, the query rows, then the tiles
+    // that are only needed a little later (loads return in order).
+    if (n_tiles > 0) issue_tile(0);
+    load_q_raw();
+    __builtin_amdgcn_sched_barrier(0);
+    for (int t = 1; t < kStages - 1 && t < n_tiles; ++t) issue_tile(t);
+    __builtin_amdgcn_sched_barrier(0);
+    {
+        // Per-row temperature: the table is staged in the last ring buffer (first refilled during
+        // tile 0, i.e. after the lookups), so the lookup is not a second dependent trip to memory.
+        constexpr int kTauLds = kTileBytes / 4;
+        float *tau_lds = (float *)(lds + (kStages - 1) * kTileBytes);
+        const int n_tau = p.n_scen * p.n_beh;
+        const bool tau_in_lds = n_tau <= kTauLds;
+        if (tau_in_lds)
+            for (int i = tid; i < n_tau; i += NT) tau_lds[i] = p.tau[i];
+        int tau_idx[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const int sc = min(max(p.scen[qrow[qb]], 0), p.n_scen - 1);
+            const int bhv = min(max(p.beh[qrow[qb]], 0), p.n_beh - 1);
+            tau_idx[qb] = sc * p.n_beh + bhv;
+        }
+        __syncthreads();  // tau_lds is written
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+            st.c[qb] = p.scale_log2e / (tau_in_lds ? tau_lds[tau_idx[qb]] : p.tau[tau_idx[qb]]);
+    }
     init_state(std::false_type{});
-    if (n_tiles > 0) {
+    unsigned own_touch[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) own_touch[qb] = 0;
+    if (!PIPE) {
+        for (int t = 0; t < n_tiles; ++t) {
+            wait_tiles<NPRE>(min(t + kStages - 1, n_tiles) - (t + 1));
+            __builtin_amdgcn_s_barrier();
+            if (t + kStages - 1 < n_tiles) issue_tile(t + kStages - 1);
+            const uint8_t *cur = lds + (t % kStages) * kTileBytes;
+            const int tile_lo = k_lo + t * kTileKeys;
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk) {
+                const int blk_lo = tile_lo + blk * kBlockKeys;
+                if (blk_lo < k_hi) {
+                    f32x16 S[QB];
+                    bf16x8 P[QB][2];
+                    const KFrags kf = load_k(cur + blk * kBlockBytes, lane);
+                    qk_block(st, kf, S);
+                    if (blk_lo + kBlockKeys > k_hi) mask_block(S, hf, blk_lo, k_hi);
+                    softmax_fast(st, S, P);
+                    const VFrags vf = load_v(cur + blk * kBlockBytes, lane);
+                    pv_block(st, vf, P);
+                }
+            }
+        }
+    } else if (n_tiles > 0) {
         f32x16 S0[QB], S1[QB];
         bf16x8 P[QB][2];
         wait_tiles<NPRE>(min(kStages - 1, n_tiles) - 1);
@@ -412,6 +482,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             qk_block(st, k0, S0);
         }
         for (int t = 0; t + 1 < n_tiles; ++t) {  // every tile but the last: 64 unmasked keys
+            if (SUMI && t == n_tiles / 2) {
+                // Half-way: touch the cache lines of the candidates' own key / value rows (one
+                // dword per 128-byte line: half-wave 0 the key line, half-wave 1 the value line)
+                // so that add_own_fast finds them in L2 instead of paying a trip to HBM.
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    own_touch[qb] = *(const unsigned *)((hf ? p.v_self : p.k_self) + qrow[qb] * p.ld_kv + h * kDHead);
+            }
             const uint8_t *cur = lds + (t % kStages) * kTileBytes;
             const uint8_t *nxt = lds + ((t + 1) % kStages) * kTileBytes;
             {   // block 0 of tile t: its logits are in S0; start block 1's logits
@@ -456,6 +534,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         }
     }
 
+    if (SUMI) add_own_fast();
+    // keep the touch loads alive without ever storing anything (a float denominator is never NaN-
+    // equal to itself): their only purpose is the cache fill
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+        if (st.l[qb] != st.l[qb] && own_touch[qb] == 0x7fc01234u) st.l[qb] = 0.f;
+
     // ---- SAFE pass (rare): whole workgroup redoes its rows with a running maximum -----------
     float lt[QB];
     bool bad = false;
@@ -466,6 +551,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     }
     if (__syncthreads_or(bad)) {  // also orders the reuse of the LDS ring
         prologue();
+        load_q_raw();
         init_state(std::true_type{});
         for (int t = 0; t < n_tiles; ++t) {
             wait_tiles<NPRE>(min(t + kStages - 1, n_tiles) - (t + 1));
@@ -557,7 +643,7 @@ KParams make_params(const AttnArgs &a, int n_qtiles)
     return p;
 }
 
-template <int NW, int QB, bool SUMI>
+template <int NW, int QB, bool SUMI, int kStages = 4, bool PIPE = true, int WPS = 2>
 hipError_t launch(const AttnArgs &a, hipStream_t s)
 {
     constexpr int TQ = NW * 32 * QB;
@@ -566,7 +652,7 @@ hipError_t launch(const AttnArgs &a, hipStream_t s)
     const int64_t grid = (int64_t)8 * n_qtiles * groups;
     if (grid <= 0 || grid > 0x7fffffff) return hipErrorInvalidValue;
     const KParams p = make_params(a, n_qtiles);
-    hipLaunchKernelGGL((attn_bf16_kernel<NW, QB, SUMI, 4>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<NW, QB, SUMI, kStages, PIPE, WPS>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -589,6 +675,8 @@ hipError_t dispatch(const AttnArgs &a, int tile, hipStream_t s)
     switch (tile) {
     case 22: return launch<2, 2, SUMI>(a, s);
     case 41: return launch<4, 1, SUMI>(a, s);
+    case 423: return launch<4, 2, SUMI, 3, false, 3>(a, s);
+    case 424: return launch<4, 2, SUMI, 4, false, 2>(a, s);
     case 82: return launch<8, 2, SUMI>(a, s);
     default: return launch<4, 2, SUMI>(a, s);
     }
@@ -608,7 +696,7 @@ hipError_t launch_attn_hist_bf16(const AttnArgs &a, hipStream_t s)
     // a query tile must lie inside one subsequence (sub_len is 0 or a multiple of 128)
     int tile = forced_tile();
     if (tile == 0) tile = 42;
-    const int tq = (tile / 10) * 32 * (tile % 10);
+    const int tq = tile > 100 ? 256 : (tile / 10) * 32 * (tile % 10);
     if (a.sub_len % tq != 0) tile = 41;
     return dispatch<false>(a, tile, s);
 }
