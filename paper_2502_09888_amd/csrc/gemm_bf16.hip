@@ -4,11 +4,16 @@
 //
 // W is first repacked (pack_weight) into B-operand fragments of v_mfma_f32_32x32x16_bf16:
 //   chunk (nb, ks, lane), 16 B: W[16ks + 8(lane/32) + 0..7][32nb + lane%32]
-// so that the GEMM copies it HBM -> LDS linearly and every wave reads a fragment as one
-// conflict-free 16-byte-per-lane access.  A stays row-major; its LDS tile is XOR-swizzled in
-// 16-byte chunks so that the fragment reads (32 rows, same k chunk) spread over all banks.
-// Tile: 128 x 128 x 64 per 256-thread workgroup, 4 waves as 2 x 2, each 64 x 64 = 2 x 2 MFMA
-// blocks, LDS double buffer (64 KiB), one barrier per k-tile.
+// so that a k-tile of a 32-column block is contiguous and is copied HBM -> LDS linearly.
+// A stays row-major; its tile is copied row by row (64 B per row and k-tile) with the 16-byte
+// chunks of a row XOR-swizzled through the choice of the global address each lane loads, so that
+// the fragment reads (32 rows, same k chunk) are conflict free.
+// Both copies are direct global_load_lds (no register staging) into a ring of 4 k-tiles of 32,
+// two to three tiles in flight, one bare s_barrier per k-tile.
+// Workgroup = 4 waves as 2 x 2; a wave owns WM x WN blocks of 32 x 32:
+//   4 x 4 (macro tile 256 x 256): half an LDS fragment read per MFMA -- the shape that keeps the
+//         matrix pipe, not LDS bandwidth, the limit; accumulators (256 registers) live in AGPRs;
+//   2 x 2 (macro tile 128 x 128): for problems too small to fill the chip with 256 x 256 tiles.
 #include "gemm.h"
 
 namespace climber {
@@ -16,9 +21,11 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
+typedef const __attribute__((address_space(1))) uint8_t glb_u8;
 
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int kStageBytes = (BM * BK + BN * BK) * 2;  // 32 KiB
+constexpr int BK = 32;      // k-tile
+constexpr int kStages = 4;  // LDS ring
 
 __global__ __launch_bounds__(256) void pack_weight_kernel(const __bf16 *w, __bf16 *out, int K, int N)
 {
@@ -36,106 +43,194 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const __bf16 *w, __bf1
     ((uint4 *)out)[chunk] = *(const uint4 *)v;
 }
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
-
-template <int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const __bf16 *A, int64_t lda,
-                                                           const __bf16 *Wp, int M, int N, int K,
-                                                           void *C, int64_t ldc, const float *resid,
-                                                           int64_t ldr)
+// exact-erf GELU, erf by the rational/exponential formula 7.1.26 of Abramowitz & Stegun
+// (|error| <= 1.5e-7, far below the bf16 rounding of the result)
+__device__ __forceinline__ float gelu_erf(float x)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kStageBytes];
+    const float z = fabsf(x) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.f));
+    float poly = fmaf(1.061405429f, t, -1.453152027f);
+    poly = fmaf(poly, t, 1.421413741f);
+    poly = fmaf(poly, t, -0.284496736f);
+    poly = fmaf(poly, t, 0.254829592f);
+    const float e = __builtin_amdgcn_exp2f(-z * z * 1.4426950408889634f);
+    const float erf_abs = 1.f - poly * t * e;
+    const float erf_x = x < 0.f ? -erf_abs : erf_abs;
+    return 0.5f * x * (1.f + erf_x);
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm()
+{
+    if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else static_assert(N == 0 || N == 2 || N == 4 || N == 8 || N == 16, "unsupported vmcnt");
+}
+
+// WM, WN: 32 x 32 blocks per wave along M and N.  Macro tile (2*WM*32) x (2*WN*32) x 32.
+template <int EPI, int WM, int WN>
+__global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
+    const __bf16 *A, int64_t lda, const __bf16 *Wp, int M, int N, int K, void *C, int64_t ldc,
+    const float *resid, int64_t ldr)
+{
+    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int kABytes = BM * BK * 2, kBBytes = BN * BK * 2, kStageBytes = kABytes + kBBytes;
+    constexpr int NA = kABytes / 1024 / 4, NB = kBBytes / 1024 / 4;  // 1 KiB copies per wave and tile
+    constexpr int NPRE = NA + NB;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const int n_kt = K / BK;
-    const int64_t kchunks = (int64_t)(K / 16) * 64;  // 16-byte chunks per 32-column block of Wp
 
-    // per-thread copy plan: 4 A chunks and 4 W chunks per k-tile
-    const __bf16 *a_src[4];
-    int a_dst[4];
-    const uint4 *w_src[4];
+    // copy plan.  A: copy j of this wave covers rows 16*(wave*NA + j) .. +15, lane -> (row, slot),
+    // global chunk = slot ^ ((row >> 1) & 3).  W: copy j covers fragment (nbl, ksl) of the tile.
+    const __bf16 *a_src[NA];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int q = tid + 256 * i;
-        const int row = q >> 3, c = q & 7;
-        a_src[i] = A + (int64_t)min(m0 + row, M - 1) * lda + c * 8;
-        a_dst[i] = row * 128 + ((c ^ (row & 7)) * 16);
-        const int nbl = q >> 8, rem = q & 255;
-        w_src[i] = (const uint4 *)Wp + ((int64_t)(n0 / 32 + nbl) * kchunks + rem);
+    for (int j = 0; j < NA; ++j) {
+        const int r = 16 * (wave * NA + j) + (lane >> 2), slot = lane & 3;
+        a_src[j] = A + (int64_t)min(m0 + r, M - 1) * lda + ((slot ^ ((r >> 1) & 3)) * 8);
     }
-    f32x16 acc[2][2];
+    const uint8_t *w_src[NB];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < NB; ++j) {
+        const int f = wave * NB + j, nbl = f >> 1, ksl = f & 1;
+        w_src[j] = (const uint8_t *)Wp +
+                   (((int64_t)(n0 / 32 + nbl) * (K / 16) + ksl) * 64 + lane) * 16;
+    }
+    auto issue = [&](int kt) __attribute__((always_inline)) {
+        lds_u8 *base = (lds_u8 *)lds + (kt % kStages) * kStageBytes;
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NA; ++j)
+            __builtin_amdgcn_global_load_lds((glb_u8 *)(a_src[j] + kt * BK),
+                                             base + (wave * NA + j) * 1024, 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            __builtin_amdgcn_global_load_lds((glb_u8 *)(w_src[j] + (int64_t)kt * 2048),
+                                             base + kABytes + (wave * NB + j) * 1024, 16, 0, 0);
+    };
+
+    f32x16 acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    uint4 pa[4], pw[4];
-    auto fetch = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            pa[i] = *(const uint4 *)(a_src[i] + kt * BK);
-            pw[i] = w_src[i][(int64_t)kt * 256];
-        }
-    };
-    auto stash = [&](int buf) {
-        uint8_t *base = lds + buf * kStageBytes;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *(uint4 *)(base + a_dst[i]) = pa[i];
-            ((uint4 *)(base + BM * BK * 2))[tid + 256 * i] = pw[i];
-        }
-    };
-    fetch(0);
-    stash(0);
-    __syncthreads();
+    for (int kt = 0; kt < kStages - 1 && kt < n_kt; ++kt) issue(kt);
     for (int kt = 0; kt < n_kt; ++kt) {
-        const uint8_t *sa = lds + (kt & 1) * kStageBytes;
-        const uint8_t *sw = sa + BM * BK * 2;
-        const bool more = kt + 1 < n_kt;
-        if (more) fetch(kt + 1);
+        // tiles kt+1 .. kt+kStages-2 may stay in flight
+        const int ahead = min(kt + kStages - 1, n_kt) - (kt + 1);
+        if (ahead >= 2) wait_vm<2 * NPRE>();
+        else if (ahead == 1) wait_vm<NPRE>();
+        else wait_vm<0>();
+        __builtin_amdgcn_s_barrier();
+        if (kt + kStages - 1 < n_kt) issue(kt + kStages - 1);
+        const uint8_t *sa = lds + (kt % kStages) * kStageBytes;
+        const uint8_t *sw = sa + kABytes;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 af[2], bfr[2];
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 af[WM], bfr[WN];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int row = 64 * wm + 32 * i + l32;
-                af[i] = *(const bf16x8 *)(sa + row * 128 + (((2 * ks + hf) ^ (row & 7)) * 16));
-                bfr[i] = *(const bf16x8 *)(sw + (((2 * wn + i) * 256) + ks * 64 + lane) * 16);
+            for (int i = 0; i < WM; ++i) {
+                const int row = 32 * (WM * wm + i) + l32;
+                af[i] = *(const bf16x8 *)(sa + row * 64 + (((2 * ks + hf) ^ ((row >> 1) & 3)) * 16));
             }
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int j = 0; j < WN; ++j)
+                bfr[j] = *(const bf16x8 *)(sw + (((WN * wn + j) * 2 + ks) * 64 + lane) * 16);
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
-        if (more) stash((kt + 1) & 1);
-        __syncthreads();
     }
 
-    // epilogue: lane holds D[8(r/4) + 4hf + r%4][l32] of each 32 x 32 block
+    // Epilogue.  The operands were fed as (W fragment, A fragment), so a block accumulator is the
+    // transposed product: lane holds C[32i + l32][32j + 8g + 4hf + 0..3] for g = r/4 -- four
+    // consecutive columns of ONE row.  Each wave turns 32 rows x (WN*32) columns around in its own
+    // corner of the (now idle) LDS ring and stores whole rows, 16 bytes per lane.
+    __syncthreads();  // every wave is done reading the last k-tile
+    constexpr bool F32 = EPI == EPI_RESID_F32;
+    constexpr int CW = WN * 32;                       // columns of a wave's block
+    constexpr int kElem = F32 ? 4 : 2;
+    constexpr int kPitch = CW * kElem + 16;           // bytes per staged row
+    constexpr int kChunksPerRow = CW * kElem / 16;
+    uint8_t *tr = lds + wave * (32 * kPitch);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < WM; ++i) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int col = n0 + 64 * wn + 32 * j + l32;
+        for (int j = 0; j < WN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + 64 * wm + 32 * i + 8 * (r >> 2) + 4 * hf + (r & 3);
-                if (row < M) {
-                    const float v = acc[i][j][r];
-                    if (EPI == EPI_STORE_BF16)
-                        ((__bf16 *)C)[(int64_t)row * ldc + col] = (__bf16)v;
-                    else if (EPI == EPI_GELU_BF16)
-                        ((__bf16 *)C)[(int64_t)row * ldc + col] = (__bf16)gelu_erf(v);
-                    else
-                        ((float *)C)[(int64_t)row * ldc + col] = v + resid[(int64_t)row * ldr + col];
+            for (int g = 0; g < 4; ++g) {
+                const int col = 32 * j + 8 * g + 4 * hf;
+                if (F32) {
+                    float4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                    *(float4 *)(tr + l32 * kPitch + col * 4) = v;
+                } else {
+                    __attribute__((aligned(8))) __bf16 v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float x = acc[i][j][4 * g + e];
+                        v[e] = (__bf16)(EPI == EPI_GELU_BF16 ? gelu_erf(x) : x);
+                    }
+                    *(uint2 *)(tr + l32 * kPitch + col * 2) = *(const uint2 *)v;
+                }
+            }
+        const int row_base = m0 + 32 * (WM * wm + i);
+        const int col_base = n0 + CW * wn;
+#pragma unroll
+        for (int it = 0; it < 32 * kChunksPerRow / 64; ++it) {
+            const int id = it * 64 + lane, r = id / kChunksPerRow, cc = id % kChunksPerRow;
+            const int row = row_base + r;
+            uint4 val = *(const uint4 *)(tr + r * kPitch + cc * 16);
+            if (row < M) {
+                if (F32) {
+                    const int col = col_base + cc * 4;
+                    const float4 rs = *(const float4 *)(resid + (int64_t)row * ldr + col);
+                    float4 o = *(const float4 *)&val;
+                    o.x += rs.x; o.y += rs.y; o.z += rs.z; o.w += rs.w;
+                    *(float4 *)((float *)C + (int64_t)row * ldc + col) = o;
+                } else {
+                    *(uint4 *)((__bf16 *)C + (int64_t)row * ldc + col_base + cc * 8) = val;
                 }
             }
         }
+    }
+}
+
+template <int EPI, int WM, int WN>
+hipError_t launch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, int K, void *C,
+                  int64_t ldc, const float *resid, int64_t ldr, hipStream_t s)
+{
+    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr size_t lds_bytes = (size_t)kStages * (BM + BN) * BK * 2;
+    static const hipError_t attr = hipFuncSetAttribute(
+        (const void *)gemm_bf16_kernel<EPI, WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        (int)lds_bytes);
+    if (attr != hipSuccess) return attr;
+    const dim3 grid(N / BN, (M + BM - 1) / BM), block(256);
+    hipLaunchKernelGGL((gemm_bf16_kernel<EPI, WM, WN>), grid, block, lds_bytes, s, a, lda, w, M, N, K,
+                       C, ldc, resid, ldr);
+    return hipGetLastError();
+}
+
+template <int EPI>
+hipError_t dispatch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, int K, void *C,
+                    int64_t ldc, const float *resid, int64_t ldr, hipStream_t s)
+{
+    // 256 x 256 tiles when they alone give every CU a workgroup, else 128 x 128
+    const int64_t big = (int64_t)(N / 256) * ((M + 255) / 256);
+    if (N % 256 == 0 && big >= 256)
+        return launch<EPI, 4, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
+    return launch<EPI, 2, 2>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
 }
 
 }  // namespace
@@ -152,23 +247,14 @@ hipError_t gemm_bf16(int epi, const void *A, int64_t lda, const void *w_packed, 
                      void *C, int64_t ldc, const float *resid, int64_t ldr, hipStream_t s)
 {
     if (M <= 0) return hipSuccess;
-    if (N % BN != 0 || K % BK != 0) return hipErrorInvalidValue;
-    const dim3 grid(N / BN, (M + BM - 1) / BM), block(256);
+    if (N % 128 != 0 || K % 64 != 0) return hipErrorInvalidValue;
     const __bf16 *a = (const __bf16 *)A, *w = (const __bf16 *)w_packed;
     switch (epi) {
-    case EPI_STORE_BF16:
-        hipLaunchKernelGGL(gemm_bf16_kernel<EPI_STORE_BF16>, grid, block, 0, s, a, lda, w, M, N, K, C, ldc, resid, ldr);
-        break;
-    case EPI_GELU_BF16:
-        hipLaunchKernelGGL(gemm_bf16_kernel<EPI_GELU_BF16>, grid, block, 0, s, a, lda, w, M, N, K, C, ldc, resid, ldr);
-        break;
-    case EPI_RESID_F32:
-        hipLaunchKernelGGL(gemm_bf16_kernel<EPI_RESID_F32>, grid, block, 0, s, a, lda, w, M, N, K, C, ldc, resid, ldr);
-        break;
-    default:
-        return hipErrorInvalidValue;
+    case EPI_STORE_BF16: return dispatch<EPI_STORE_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
+    case EPI_GELU_BF16: return dispatch<EPI_GELU_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
+    case EPI_RESID_F32: return dispatch<EPI_RESID_F32>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
+    default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 }  // namespace climber
