@@ -13,8 +13,13 @@
 // Workgroup = 4 waves as 2 x 2; a wave owns WM x WN blocks of 32 x 32:
 //   4 x 4 (macro tile 256 x 256): half an LDS fragment read per MFMA -- the shape that keeps the
 //         matrix pipe, not LDS bandwidth, the limit; accumulators (256 registers) live in AGPRs;
-//   2 x 2 (macro tile 128 x 128): for problems too small to fill the chip with 256 x 256 tiles.
+//   4 x 2 (macro tile 256 x 128): 128 accumulator registers, two workgroups per CU, so that one's
+//         prologue / epilogue overlaps the other's k-loop (the projections here have K = 512 or
+//         2048: short k-loops, and they sit near the HBM/MFMA ridge);
+//   2 x 2 (macro tile 128 x 128): for problems too small to fill the chip with larger tiles.
 #include "gemm.h"
+
+#include <cstdlib>
 
 namespace climber {
 namespace {
@@ -25,7 +30,6 @@ typedef __attribute__((address_space(3))) uint8_t lds_u8;
 typedef const __attribute__((address_space(1))) uint8_t glb_u8;
 
 constexpr int BK = 32;      // k-tile
-constexpr int kStages = 4;  // LDS ring
 
 __global__ __launch_bounds__(256) void pack_weight_kernel(const __bf16 *w, __bf16 *out, int K, int N)
 {
@@ -65,13 +69,15 @@ __device__ __forceinline__ void wait_vm()
     if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     else if (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
     else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else if (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else if (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
     else if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     else if (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else static_assert(N == 0 || N == 2 || N == 4 || N == 8 || N == 16, "unsupported vmcnt");
+    else static_assert(N == 0 || N == 2 || N == 4 || N == 6 || N == 8 || N == 12 || N == 16, "unsupported vmcnt");
 }
 
 // WM, WN: 32 x 32 blocks per wave along M and N.  Macro tile (2*WM*32) x (2*WN*32) x 32.
-template <int EPI, int WM, int WN>
+template <int EPI, int WM, int WN, int kStages>
 __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
     const __bf16 *A, int64_t lda, const __bf16 *Wp, int M, int N, int K, void *C, int64_t ldc,
     const float *resid, int64_t ldr)
@@ -127,8 +133,8 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
     for (int kt = 0; kt < n_kt; ++kt) {
         // tiles kt+1 .. kt+kStages-2 may stay in flight
         const int ahead = min(kt + kStages - 1, n_kt) - (kt + 1);
-        if (ahead >= 2) wait_vm<2 * NPRE>();
-        else if (ahead == 1) wait_vm<NPRE>();
+        if (kStages > 3 && ahead >= 2) wait_vm<(kStages > 3 ? 2 : 1) * NPRE>();
+        else if (ahead >= 1) wait_vm<NPRE>();
         else wait_vm<0>();
         __builtin_amdgcn_s_barrier();
         if (kt + kStages - 1 < n_kt) issue(kt + kStages - 1);
@@ -206,18 +212,18 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
     }
 }
 
-template <int EPI, int WM, int WN>
+template <int EPI, int WM, int WN, int kStages>
 hipError_t launch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, int K, void *C,
                   int64_t ldc, const float *resid, int64_t ldr, hipStream_t s)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr size_t lds_bytes = (size_t)kStages * (BM + BN) * BK * 2;
     static const hipError_t attr = hipFuncSetAttribute(
-        (const void *)gemm_bf16_kernel<EPI, WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        (const void *)gemm_bf16_kernel<EPI, WM, WN, kStages>, hipFuncAttributeMaxDynamicSharedMemorySize,
         (int)lds_bytes);
     if (attr != hipSuccess) return attr;
     const dim3 grid(N / BN, (M + BM - 1) / BM), block(256);
-    hipLaunchKernelGGL((gemm_bf16_kernel<EPI, WM, WN>), grid, block, lds_bytes, s, a, lda, w, M, N, K,
+    hipLaunchKernelGGL((gemm_bf16_kernel<EPI, WM, WN, kStages>), grid, block, lds_bytes, s, a, lda, w, M, N, K,
                        C, ldc, resid, ldr);
     return hipGetLastError();
 }
@@ -226,11 +232,16 @@ template <int EPI>
 hipError_t dispatch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, int K, void *C,
                     int64_t ldc, const float *resid, int64_t ldr, hipStream_t s)
 {
-    // 256 x 256 tiles when they alone give every CU a workgroup, else 128 x 128
-    const int64_t big = (int64_t)(N / 256) * ((M + 255) / 256);
-    if (N % 256 == 0 && big >= 256)
-        return launch<EPI, 4, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
-    return launch<EPI, 2, 2>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
+    // CLIMBER_GEMM_TILE=44|42|22 overrides the choice, for tuning
+    static const int forced = [] { const char *e = getenv("CLIMBER_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    int tile = forced;
+    if (tile == 0) {
+        const int64_t mid = (int64_t)(N / 128) * ((M + 255) / 256);
+        tile = mid >= 512 ? 42 : 22;
+    }
+    if (tile == 44 && N % 256 == 0) return launch<EPI, 4, 4, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
+    if (tile == 42) return launch<EPI, 4, 2, 3>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
+    return launch<EPI, 2, 2, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
 }
 
 }  // namespace
