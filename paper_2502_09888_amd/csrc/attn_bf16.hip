@@ -44,6 +44,7 @@ typedef const __attribute__((address_space(1))) uint8_t glb_u8;
 
 constexpr int kTileKeys = 64;                // keys per LDS tile = 2 cache blocks
 constexpr int kTileBytes = 2 * kBlockBytes;  // 16 KiB
+constexpr int kStages = 4;                   // LDS ring of K/V tiles
 constexpr float kSafeSlack = 8.0f;           // SAFE: exp2-domain slack before the row maximum moves
 constexpr float kDenomHi = 1.0e12f;          // FAST is accepted iff kDenomLo < denominator < kDenomHi
 constexpr float kDenomLo = 1.0e-12f;
@@ -229,8 +230,8 @@ __device__ __forceinline__ void wait_tiles(int tiles_in_flight)
     }
 }
 
-template <int NW, int QB, bool SUMI, int kStages, bool PIPE, int WPS>
-__global__ __launch_bounds__(NW * 64, WPS) void attn_bf16_kernel(const KParams p)
+template <int NW, int QB, bool SUMI>
+__global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 {
     static_assert(kStages >= 3, "tile t+1 is read while tile t is computed and one more is in flight");
     constexpr int NT = NW * 64;
@@ -420,59 +421,45 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_bf16_kernel(const KParams p
     // ---- FAST pass, software pipelined over 32-key blocks -----------------------------------
     // Start-up order = what the first MFMA needs first: tile 0, the query rows, then the tiles
     // that are only needed a little later (loads return in order).
+    // ... and the row ids and the temperature table, whose values are needed together with the
+    // query rows.  The table is staged in the last ring buffer (first refilled during tile 0, i.e.
+    // after the lookups), so the per-row lookup is not a second dependent trip to memory.
+    constexpr int kTauLds = kTileBytes / 4;
+    float *tau_lds = (float *)(lds + (kStages - 1) * kTileBytes);
+    const int n_tau = p.n_scen * p.n_beh;
+    const bool tau_in_lds = n_tau <= kTauLds;
     if (n_tiles > 0) issue_tile(0);
     load_q_raw();
+    int tau_idx[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) tau_idx[qb] = p.scen[qrow[qb]];
+    int beh_id[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) beh_id[qb] = p.beh[qrow[qb]];
+    float tau_first = 0.f;
+    if (tau_in_lds && tid < n_tau) tau_first = p.tau[tid];
     __builtin_amdgcn_sched_barrier(0);
     for (int t = 1; t < kStages - 1 && t < n_tiles; ++t) issue_tile(t);
     __builtin_amdgcn_sched_barrier(0);
-    {
-        // Per-row temperature: the table is staged in the last ring buffer (first refilled during
-        // tile 0, i.e. after the lookups), so the lookup is not a second dependent trip to memory.
-        constexpr int kTauLds = kTileBytes / 4;
-        float *tau_lds = (float *)(lds + (kStages - 1) * kTileBytes);
-        const int n_tau = p.n_scen * p.n_beh;
-        const bool tau_in_lds = n_tau <= kTauLds;
-        if (tau_in_lds)
-            for (int i = tid; i < n_tau; i += NT) tau_lds[i] = p.tau[i];
-        int tau_idx[QB];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            const int sc = min(max(p.scen[qrow[qb]], 0), p.n_scen - 1);
-            const int bhv = min(max(p.beh[qrow[qb]], 0), p.n_beh - 1);
-            tau_idx[qb] = sc * p.n_beh + bhv;
-        }
-        __syncthreads();  // tau_lds is written
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-            st.c[qb] = p.scale_log2e / (tau_in_lds ? tau_lds[tau_idx[qb]] : p.tau[tau_idx[qb]]);
+    if (tau_in_lds) {
+        if (tid < n_tau) tau_lds[tid] = tau_first;
+        for (int i = tid + NT; i < n_tau; i += NT) tau_lds[i] = p.tau[i];
     }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int sc = min(max(tau_idx[qb], 0), p.n_scen - 1);
+        const int bhv = min(max(beh_id[qb], 0), p.n_beh - 1);
+        tau_idx[qb] = sc * p.n_beh + bhv;
+    }
+    // tau_lds visible to the workgroup: own LDS writes done, then a bare barrier (a fence would
+    // also wait for the K/V tiles that are meant to stay in flight)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+        st.c[qb] = p.scale_log2e / (tau_in_lds ? tau_lds[tau_idx[qb]] : p.tau[tau_idx[qb]]);
     init_state(std::false_type{});
-    unsigned own_touch[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) own_touch[qb] = 0;
-    if (!PIPE) {
-        for (int t = 0; t < n_tiles; ++t) {
-            wait_tiles<NPRE>(min(t + kStages - 1, n_tiles) - (t + 1));
-            __builtin_amdgcn_s_barrier();
-            if (t + kStages - 1 < n_tiles) issue_tile(t + kStages - 1);
-            const uint8_t *cur = lds + (t % kStages) * kTileBytes;
-            const int tile_lo = k_lo + t * kTileKeys;
-#pragma unroll
-            for (int blk = 0; blk < 2; ++blk) {
-                const int blk_lo = tile_lo + blk * kBlockKeys;
-                if (blk_lo < k_hi) {
-                    f32x16 S[QB];
-                    bf16x8 P[QB][2];
-                    const KFrags kf = load_k(cur + blk * kBlockBytes, lane);
-                    qk_block(st, kf, S);
-                    if (blk_lo + kBlockKeys > k_hi) mask_block(S, hf, blk_lo, k_hi);
-                    softmax_fast(st, S, P);
-                    const VFrags vf = load_v(cur + blk * kBlockBytes, lane);
-                    pv_block(st, vf, P);
-                }
-            }
-        }
-    } else if (n_tiles > 0) {
+    if (n_tiles > 0) {
         f32x16 S0[QB], S1[QB];
         bf16x8 P[QB][2];
         wait_tiles<NPRE>(min(kStages - 1, n_tiles) - 1);
@@ -482,14 +469,6 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_bf16_kernel(const KParams p
             qk_block(st, k0, S0);
         }
         for (int t = 0; t + 1 < n_tiles; ++t) {  // every tile but the last: 64 unmasked keys
-            if (SUMI && t == n_tiles / 2) {
-                // Half-way: touch the cache lines of the candidates' own key / value rows (one
-                // dword per 128-byte line: half-wave 0 the key line, half-wave 1 the value line)
-                // so that add_own_fast finds them in L2 instead of paying a trip to HBM.
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    own_touch[qb] = *(const unsigned *)((hf ? p.v_self : p.k_self) + qrow[qb] * p.ld_kv + h * kDHead);
-            }
             const uint8_t *cur = lds + (t % kStages) * kTileBytes;
             const uint8_t *nxt = lds + ((t + 1) % kStages) * kTileBytes;
             {   // block 0 of tile t: its logits are in S0; start block 1's logits
@@ -535,11 +514,6 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_bf16_kernel(const KParams p
     }
 
     if (SUMI) add_own_fast();
-    // keep the touch loads alive without ever storing anything (a float denominator is never NaN-
-    // equal to itself): their only purpose is the cache fill
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-        if (st.l[qb] != st.l[qb] && own_touch[qb] == 0x7fc01234u) st.l[qb] = 0.f;
 
     // ---- SAFE pass (rare): whole workgroup redoes its rows with a running maximum -----------
     float lt[QB];
@@ -643,7 +617,7 @@ KParams make_params(const AttnArgs &a, int n_qtiles)
     return p;
 }
 
-template <int NW, int QB, bool SUMI, int kStages = 4, bool PIPE = true, int WPS = 2>
+template <int NW, int QB, bool SUMI>
 hipError_t launch(const AttnArgs &a, hipStream_t s)
 {
     constexpr int TQ = NW * 32 * QB;
@@ -652,14 +626,14 @@ hipError_t launch(const AttnArgs &a, hipStream_t s)
     const int64_t grid = (int64_t)8 * n_qtiles * groups;
     if (grid <= 0 || grid > 0x7fffffff) return hipErrorInvalidValue;
     const KParams p = make_params(a, n_qtiles);
-    hipLaunchKernelGGL((attn_bf16_kernel<NW, QB, SUMI, kStages, PIPE, WPS>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<NW, QB, SUMI>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
     return hipGetLastError();
 }
 
-// Query-tile shape: NW waves x QB blocks of 32 queries per workgroup.  Wide tiles re-read a head's
-// K/V from L2 fewer times and reuse every LDS fragment for two MFMAs; narrow ones keep two waves
-// per SIMD busy when a head has few queries.  CLIMBER_ATTN_TILE=<NW><QB> (e.g. 42) overrides the
-// choice, for tuning.
+// Query-tile shape: 4 waves x QB blocks of 32 queries per workgroup.  QB = 2 (256 queries) re-reads
+// a head's K/V from L2 half as often and reuses every LDS fragment for two MFMAs; QB = 1 (128
+// queries) keeps two waves per SIMD busy when a head has few queries.  CLIMBER_ATTN_TILE=41|42
+// overrides the choice, for tuning.
 int forced_tile()
 {
     static const int v = [] {
@@ -672,14 +646,8 @@ int forced_tile()
 template <bool SUMI>
 hipError_t dispatch(const AttnArgs &a, int tile, hipStream_t s)
 {
-    switch (tile) {
-    case 22: return launch<2, 2, SUMI>(a, s);
-    case 41: return launch<4, 1, SUMI>(a, s);
-    case 423: return launch<4, 2, SUMI, 3, false, 3>(a, s);
-    case 424: return launch<4, 2, SUMI, 4, false, 2>(a, s);
-    case 82: return launch<8, 2, SUMI>(a, s);
-    default: return launch<4, 2, SUMI>(a, s);
-    }
+    if (tile == 41) return launch<4, 1, SUMI>(a, s);
+    return launch<4, 2, SUMI>(a, s);
 }
 
 }  // namespace
@@ -696,7 +664,7 @@ hipError_t launch_attn_hist_bf16(const AttnArgs &a, hipStream_t s)
     // a query tile must lie inside one subsequence (sub_len is 0 or a multiple of 128)
     int tile = forced_tile();
     if (tile == 0) tile = 42;
-    const int tq = tile > 100 ? 256 : (tile / 10) * 32 * (tile % 10);
+    const int tq = (tile / 10) * 32 * (tile % 10);
     if (a.sub_len % tq != 0) tile = 41;
     return dispatch<false>(a, tile, s);
 }
