@@ -41,6 +41,69 @@ def measured_traffic():
     return None
 
 
+def bench_stack(args, torch, P, W):
+    """Configuration 4: 4 layers, d_model 512, FFN 2048, B=32, L=1024 (4 x 256), M=256.  One step =
+    history encode (fills the 4-layer KV cache) + candidate scoring through all layers."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from harness import GpuStack, oracle_stack_users
+    spec = W.CONFIG4
+    w = W.make_stack(spec)
+    g = GpuStack(w)
+    y = torch.empty((g.m_total, spec.d_model), dtype=torch.float32, device="cuda:0")
+
+    def score():
+        P.climber_sumi_score(g.cfg, g.layers, g.tau, g.cache, g.x_cand, g.cand_off, g.m_total,
+                             g.m_max, g.cscen, g.cbeh, y, g.ws)
+
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    for _ in range(args.warmup):
+        g.encode()
+        score()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g.encode()
+        score()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    enc_ms, sc_ms = timed(g.encode, args.steps), timed(score, args.steps)
+    T, M = int(w["tok_off"][-1]), g.m_total
+    d, F, NL = spec.d_model, spec.d_ffn, spec.n_layers
+    per_row = 2.0 * (3 * d * d + d * d + 2 * d * F)
+    flop_hist = per_row * T * (NL - 1) + 2.0 * T * 3 * d * d     # last layer stops after K/V
+    flop_cand = per_row * M * NL
+    attn_hist = 4.0 * spec.sub_len * spec.dh * spec.H * T * (NL - 1)
+    attn_cand = 4.0 * (spec.L + 1) * spec.dh * spec.H * M * NL
+    ref, _ = oracle_stack_users(w, (0,))
+    err = float(abs(y[: spec.M].cpu().numpy() - ref).max())
+    achieved = (flop_hist + flop_cand + attn_hist + attn_cand) / (ms_per_step * 1e-3) / 1e12
+    out = {"metric": "candidates scored/sec/GPU, full 4-layer stack (configuration 4)",
+           "value": M / (ms_per_step * 1e-3), "unit": "candidates/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": "config4: full Climber block stack, history encode + candidate "
+                                  "scoring", "B": spec.B, "L": spec.L, "sub_len": spec.sub_len,
+                      "M": spec.M, "layers": NL, "d_model": d, "d_ffn": F},
+           "roofline": {"bound": "mfma", "kernel": "whole step (GEMM + attention flop)",
+                        "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None},
+           "breakdown": {"encode_ms": enc_ms, "score_ms": sc_ms,
+                         "gemm_tflops_encode": flop_hist / (enc_ms * 1e-3) / 1e12,
+                         "gemm_tflops_score": flop_cand / (sc_ms * 1e-3) / 1e12},
+           "parity_max_abs_vs_oracle": err}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,6 +113,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle cpu_baseline leg")
     ap.add_argument("--no-naive", action="store_true", help="skip the naive re-encode baseline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--workload", choices=["attention", "stack"], default="attention",
+                    help="attention = configuration 3 (the headline metric); stack = configuration 4, "
+                         "the full 4-layer block stack (extra line, same JSON shape)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (users shard across GPUs without any "
@@ -65,6 +131,8 @@ def main():
         print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
         sys.exit(3)
     P.load_library()
+    if args.workload == "stack":
+        return bench_stack(args, torch, P, W)
     dev = "cuda:0"
     spec = W.CONFIG3
     w = W.make_attention(spec)
