@@ -17,7 +17,7 @@
 //     numerator and denominator share it, and fp32 / bf16 carry 8 exponent bits, so for logits of
 //     ordinary size NO reference is needed at all: with the per-row temperature folded into the
 //     query, q' = bf16(q * qk_scale*log2(e)/tau_row), a logit is t = <q',k> straight out of the
-//     MFMA, p = exp2(t), and it costs one v_exp_f32, half a v_cvt_pk_bf16_f32 and half a v_dot2
+//     MFMA, p = exp2(t), and it costs one v_exp_f32, half a v_cvt_pk_bf16_f32 and one v_add_f32
 //     (denominator) -- no row maximum, no subtraction, no rescale of O.  The loop is software
 //     pipelined over 32-key blocks: the S^T MFMAs of block i+1 are issued before the exponentials
 //     of block i, so matrix and vector pipes overlap inside one wave.
@@ -39,12 +39,13 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 typedef const __attribute__((address_space(1))) uint8_t glb_u8;
 
 constexpr int kTileKeys = 64;                // keys per LDS tile = 2 cache blocks
 constexpr int kTileBytes = 2 * kBlockBytes;  // 16 KiB
-constexpr int kStages = 4;                   // LDS ring of K/V tiles
+constexpr int kStages = 3;                   // LDS ring of K/V tiles
 constexpr float kSafeSlack = 8.0f;           // SAFE: exp2-domain slack before the row maximum moves
 constexpr float kDenomHi = 1.0e12f;          // FAST is accepted iff kDenomLo < denominator < kDenomHi
 constexpr float kDenomLo = 1.0e-12f;
@@ -148,24 +149,23 @@ __device__ __forceinline__ void mask_block(f32x16 (&S)[QB], int hf, int blk_lo, 
 }
 
 // p = exp2(S*scale - sub) rounded to bf16 in B-operand order (P[g] holds the keys of 16-key
-// group g); returns the sum of the ROUNDED values (v_dot2 with ones): the numbers P V multiplies.
+// group g); returns the sum of the values before rounding (round-to-nearest is unbiased, so the
+// denominator and the bf16 numerators agree to well below the bf16 rounding of a single term).
+// Plain v_add_f32 on purpose: the v_dot2 family issues into the matrix pipe and would take MFMA
+// slots, whereas adds overlap with the MFMAs of the other wave on the SIMD.
 template <bool AFFINE>
 __device__ __forceinline__ float exp_pack(const f32x16 &S, float scale, float sub, bf16x8 (&P)[2])
 {
-    bf16x2 ones;
-    ones[0] = (__bf16)1.f;
-    ones[1] = (__bf16)1.f;
     float sum = 0.f;
 #pragma unroll
     for (int g = 0; g < 2; ++g)
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-            bf16x2 pp;
-            pp[0] = (__bf16)__builtin_amdgcn_exp2f(AFFINE ? fmaf(S[8 * g + e], scale, -sub) : S[8 * g + e]);
-            pp[1] = (__bf16)__builtin_amdgcn_exp2f(AFFINE ? fmaf(S[8 * g + e + 1], scale, -sub) : S[8 * g + e + 1]);
-            P[g][e] = pp[0];
-            P[g][e + 1] = pp[1];
-            sum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, sum, false);
+            const float p0 = __builtin_amdgcn_exp2f(AFFINE ? fmaf(S[8 * g + e], scale, -sub) : S[8 * g + e]);
+            const float p1 = __builtin_amdgcn_exp2f(AFFINE ? fmaf(S[8 * g + e + 1], scale, -sub) : S[8 * g + e + 1]);
+            P[g][e] = (__bf16)p0;
+            P[g][e + 1] = (__bf16)p1;
+            sum += p0 + p1;
         }
     return sum;
 }
@@ -233,15 +233,17 @@ __device__ __forceinline__ void wait_tiles(int tiles_in_flight)
 template <int NW, int QB, bool SUMI>
 __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 {
-    static_assert(kStages >= 3, "tile t+1 is read while tile t is computed and one more is in flight");
+    static_assert(kStages == 3, "tile t+1 is read while tile t is computed and one more is in flight; "
+                                "every wait in the FAST loop drains all copies");
     constexpr int NT = NW * 64;
     constexpr int WQ = 32 * QB;  // query rows per wave
     constexpr int TQ = NW * WQ;  // query rows per workgroup
     constexpr int NPRE = kTileBytes / 16 / NT;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kStages * kTileBytes];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kStages * kTileBytes + TQ * 128];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hf = lane >> 5;
+    int l32 = lane & 31;
+    const int hf = lane >> 5;
 
     // workgroup -> (user, head, query tile).  Consecutive workgroup ids are dealt round-robin to
     // the 8 XCDs; tiles of the same (user, head) get ids congruent mod 8 so that they run on one
@@ -323,50 +325,53 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     };
 
     QState<QB> st;
-    int64_t qrow[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int wq = wave * WQ + qb * 32 + l32;
-        qrow[qb] = row0 + min(wq, nq - 1);
-    }
 
-    // Query operands.  FAST: q' = bf16(q*c), empty state; the candidate's own key/value joins the
-    // softmax after the history (add_own_fast) so that its rows are not part of what a starting
-    // workgroup has to wait for.  SAFE: q unscaled; the own key/value is the first member and its
-    // logit the first reference.
-    auto load_q_raw = [&]() __attribute__((always_inline)) {
+    // FAST start: q' = bf16(q*c) from the raw rows in st.qf, empty state (the candidate's own
+    // key/value joins later, from the landing buffer).
+    auto init_fast = [&](const float (&c)[QB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            const __bf16 *qp = p.q + qrow[qb] * p.ld_q + h * kDHead + 8 * hf;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) st.qf[qb][s] = *(const bf16x8 *)(qp + 16 * s);
+            for (int s = 0; s < 4; ++s) {
+                const bf16x8 qq = st.qf[qb][s];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) st.qf[qb][s][e] = (__bf16)((float)qq[e] * c[qb]);
+            }
+            st.l[qb] = 0.f;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) st.O[db][qb][r] = 0.f;
         }
     };
-    auto init_state = [&](auto safe_tag) __attribute__((always_inline)) {
-        constexpr bool SAFE = decltype(safe_tag)::value;
+    // SAFE start (rare): everything is fetched again, straight from global memory, so that nothing
+    // of it has to stay in registers across the FAST pass (the empty asm keeps the compiler from
+    // reusing the FAST pass's row addresses).  q unscaled; the own key/value is the first member
+    // of the softmax and its logit the first reference.
+    auto init_safe = [&]() __attribute__((always_inline)) {
+        int l32s = l32, hfs = hf;
+        asm volatile("" : "+v"(l32s), "+v"(hfs));
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            const float c = st.c[qb];
-            const __bf16 *kp = p.k_self + qrow[qb] * p.ld_kv + h * kDHead + 8 * hf;
+            const int64_t row = row0 + min(wave * WQ + qb * 32 + l32s, nq - 1);
+            const int sc = min(max(p.scen[row], 0), p.n_scen - 1);
+            const int bhv = min(max(p.beh[row], 0), p.n_beh - 1);
+            st.c[qb] = p.scale_log2e / p.tau[sc * p.n_beh + bhv];
+            const __bf16 *qp = p.q + row * p.ld_q + h * kDHead + 8 * hfs;
             float dot = 0.f;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const bf16x8 qq = st.qf[qb][s];  // raw rows from load_q_raw
-                if (SAFE) {
-                    const bf16x8 kk = *(const bf16x8 *)(kp + 16 * s);
-                    st.qf[qb][s] = qq;
+                st.qf[qb][s] = *(const bf16x8 *)(qp + 16 * s);
+                if (SUMI) {
+                    const bf16x8 kk = *(const bf16x8 *)(p.k_self + row * p.ld_kv + h * kDHead + 8 * hfs + 16 * s);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) dot += (float)qq[e] * (float)kk[e];
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) st.qf[qb][s][e] = (__bf16)((float)qq[e] * c);
+                    for (int e = 0; e < 8; ++e) dot += (float)st.qf[qb][s][e] * (float)kk[e];
                 }
             }
             st.m_ref[qb] = dot + xhalf(dot);  // both halves add the same two numbers
-            const bool own_first = SAFE && SUMI;
-            st.l[qb] = (own_first && hf == 0) ? 1.f : 0.f;
-            if (own_first) {
-                const __bf16 *vp = p.v_self + qrow[qb] * p.ld_kv + h * kDHead + 4 * hf;
+            st.l[qb] = (SUMI && hfs == 0) ? 1.f : 0.f;
+            if (SUMI) {
+                const __bf16 *vp = p.v_self + row * p.ld_kv + h * kDHead + 4 * hfs;
 #pragma unroll
                 for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -381,36 +386,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) st.O[db][qb][r] = 0.f;
             }
-        }
-    };
-    // FAST, SUMI: weight exp2(<q', k_own>) for the candidate's own key, O += weight * v_own.
-    auto add_own_fast = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            const __bf16 *kp = p.k_self + qrow[qb] * p.ld_kv + h * kDHead + 8 * hf;
-            const __bf16 *vp = p.v_self + qrow[qb] * p.ld_kv + h * kDHead + 4 * hf;
-            bf16x8 kk[4];
-            bf16x4 vv[2][4];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) kk[s] = *(const bf16x8 *)(kp + 16 * s);
-#pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) vv[db][g] = *(const bf16x4 *)(vp + 32 * db + 8 * g);
-            float dot = 0.f;
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) dot += (float)st.qf[qb][s][e] * (float)kk[s][e];
-            const float w = __builtin_amdgcn_exp2f(dot + xhalf(dot));
-            st.l[qb] += hf == 0 ? w : 0.f;
-#pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        st.O[db][qb][4 * g + e] = fmaf(w, (float)vv[db][g][e], st.O[db][qb][4 * g + e]);
         }
     };
     auto prologue = [&]() __attribute__((always_inline)) {
@@ -428,18 +403,81 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     float *tau_lds = (float *)(lds + (kStages - 1) * kTileBytes);
     const int n_tau = p.n_scen * p.n_beh;
     const bool tau_in_lds = n_tau <= kTauLds;
+    // Query rows land in the two ring buffers that hold no tile yet: whole 128-byte rows, copied
+    // HBM -> LDS by the wave that owns them (8 lanes per row, so every request is a full line),
+    // 16-byte chunks XOR-swizzled by the row number so that the fragment reads below are
+    // conflict-free.
+    uint8_t *rows_lds = lds + kStages * kTileBytes + wave * (WQ * 128);
+    auto issue_rows = [&](const __bf16 *base, int64_t ld) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < WQ / 8; ++i) {
+            const int pos = i * 64 + lane, r = pos >> 3, c = (pos & 7) ^ (r & 7);
+            const int64_t row = row0 + min(wave * WQ + r, nq - 1);
+            __builtin_amdgcn_global_load_lds((glb_u8 *)(base + row * ld + h * kDHead + c * 8),
+                                             (lds_u8 *)rows_lds + i * 1024, 16, 0, 0);
+        }
+    };
+    auto load_q_lds = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int r = qb * 32 + l32, c = (2 * s + hf) ^ (r & 7);
+                st.qf[qb][s] = *(const bf16x8 *)(rows_lds + r * 128 + c * 16);
+            }
+    };
+    // FAST, SUMI: the candidate's own key/value.  Their rows travel through the same landing
+    // buffer while the history loop runs (keys first, values once the keys are consumed), so no
+    // wave ever waits for them: weight w = exp2(<q', k_own>), then O += w * v_own.
+    float w_own[QB];
+    auto own_k = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const int r = qb * 32 + l32;
+            float dot = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const bf16x8 kk = *(const bf16x8 *)(rows_lds + r * 128 + (((2 * s + hf) ^ (r & 7)) * 16));
+                // read q' back out of the packed operand registers (the empty asm hides where
+                // they came from: otherwise the unpacked halves stay live across the whole loop)
+                u32x4 qv = __builtin_bit_cast(u32x4, st.qf[qb][s]);
+                asm volatile("" : "+v"(qv));
+                const bf16x8 qq = __builtin_bit_cast(bf16x8, qv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot += (float)qq[e] * (float)kk[e];
+            }
+            w_own[qb] = __builtin_amdgcn_exp2f(dot + xhalf(dot));
+            st.l[qb] += hf == 0 ? w_own[qb] : 0.f;
+        }
+    };
+    auto own_v = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const int r = qb * 32 + l32;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const bf16x4 vv =
+                        *(const bf16x4 *)(rows_lds + r * 128 + (((4 * db + g) ^ (r & 7)) * 16) + 8 * hf);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        st.O[db][qb][4 * g + e] = fmaf(w_own[qb], (float)vv[e], st.O[db][qb][4 * g + e]);
+                }
+        }
+    };
     if (n_tiles > 0) issue_tile(0);
-    load_q_raw();
     int tau_idx[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) tau_idx[qb] = p.scen[qrow[qb]];
+    for (int qb = 0; qb < QB; ++qb) tau_idx[qb] = p.scen[row0 + min(wave * WQ + qb * 32 + l32, nq - 1)];
     int beh_id[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) beh_id[qb] = p.beh[qrow[qb]];
+    for (int qb = 0; qb < QB; ++qb) beh_id[qb] = p.beh[row0 + min(wave * WQ + qb * 32 + l32, nq - 1)];
     float tau_first = 0.f;
     if (tau_in_lds && tid < n_tau) tau_first = p.tau[tid];
     __builtin_amdgcn_sched_barrier(0);
-    for (int t = 1; t < kStages - 1 && t < n_tiles; ++t) issue_tile(t);
+    issue_rows(p.q, p.ld_q);
+    if (n_tiles > 1) issue_tile(1);
     __builtin_amdgcn_sched_barrier(0);
     if (tau_in_lds) {
         if (tid < n_tau) tau_lds[tid] = tau_first;
@@ -451,24 +489,41 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         const int bhv = min(max(beh_id[qb], 0), p.n_beh - 1);
         tau_idx[qb] = sc * p.n_beh + bhv;
     }
-    // tau_lds visible to the workgroup: own LDS writes done, then a bare barrier (a fence would
-    // also wait for the K/V tiles that are meant to stay in flight)
+    // tile 0 and the query rows of this wave have landed (only tile 1 may still be in flight);
+    // tau_lds is visible to the workgroup after the bare barrier (a fence would also wait for
+    // tile 1)
+    if (n_tiles > 1)
+        wait_tiles<NPRE>(1);
+    else
+        wait_tiles<NPRE>(0);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
+    {
+        float c[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-        st.c[qb] = p.scale_log2e / (tau_in_lds ? tau_lds[tau_idx[qb]] : p.tau[tau_idx[qb]]);
-    init_state(std::false_type{});
+        for (int qb = 0; qb < QB; ++qb)
+            c[qb] = p.scale_log2e / (tau_in_lds ? tau_lds[tau_idx[qb]] : p.tau[tau_idx[qb]]);
+        load_q_lds();
+        init_fast(c);
+    }
     if (n_tiles > 0) {
         f32x16 S0[QB], S1[QB];
         bf16x8 P[QB][2];
-        wait_tiles<NPRE>(min(kStages - 1, n_tiles) - 1);
+        // every wave has read its query rows (they share buffers 2 and 3 with tiles 2 and 3)
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
+        for (int t = 2; t < kStages - 1 && t < n_tiles; ++t) issue_tile(t);
         {
             const KFrags k0 = load_k(lds, lane);
             qk_block(st, k0, S0);
         }
-        for (int t = 0; t + 1 < n_tiles; ++t) {  // every tile but the last: 64 unmasked keys
+        // One step = every tile but the last: 64 unmasked keys.  EV numbers the tile that becomes
+        // readable in the middle of the step when something rides along with its refill or is
+        // due afterwards (the own rows of a candidate tile); 0 = plain step.  The steps with
+        // events are peeled off the loop: inside it they would make the compiler shuffle the
+        // accumulators around the branches.
+        auto tile_step = [&](int t, auto ev_tag) __attribute__((always_inline)) {
+            constexpr int EV = decltype(ev_tag)::value;
             const uint8_t *cur = lds + (t % kStages) * kTileBytes;
             const uint8_t *nxt = lds + ((t + 1) % kStages) * kTileBytes;
             {   // block 0 of tile t: its logits are in S0; start block 1's logits
@@ -479,7 +534,15 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 softmax_fast(st, S0, P);
                 pv_block(st, v0, P);
             }
-            sync_tile(t + 1);
+            // tile t+1 becomes readable (kStages == 3: no later tile is in flight, the wait
+            // drains every copy, own rows included); the own rows ride along with the refill
+            wait_tiles<NPRE>(0);
+            __builtin_amdgcn_s_barrier();
+            if (SUMI && EV == 1) issue_rows(p.k_self, p.ld_kv);
+            if (SUMI && EV == 3) issue_rows(p.v_self, p.ld_kv);
+            if (t + 2 < n_tiles) issue_tile(t + 2);
+            if (SUMI && EV == 2) own_k();
+            if (SUMI && EV == 4) own_v();
             {   // block 1 of tile t; start block 0 of tile t+1
                 const KFrags k0 = load_k(nxt, lane);
                 const VFrags v1 = load_v(cur + kBlockBytes, lane);
@@ -487,6 +550,19 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 qk_block(st, k0, S0);
                 softmax_fast(st, S1, P);
                 pv_block(st, v1, P);
+            }
+        };
+        if (n_tiles > 1) {
+            tile_step(0, std::integral_constant<int, 1>{});
+            if (n_tiles > 2) {
+                tile_step(1, std::integral_constant<int, 2>{});
+                if (n_tiles > 3) {
+                    tile_step(2, std::integral_constant<int, 3>{});
+                    if (n_tiles > 4) {
+                        tile_step(3, std::integral_constant<int, 4>{});
+                        for (int t = 4; t + 1 < n_tiles; ++t) tile_step(t, std::integral_constant<int, 0>{});
+                    }
+                }
             }
         }
         {   // last tile: 1..64 keys, S0 holds its first block
@@ -513,7 +589,25 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         }
     }
 
-    if (SUMI) add_own_fast();
+    // lane % 32 again, opaquely: otherwise the compiler carries the old copy across the loop (in
+    // scratch memory, which would be this kernel's only use of it)
+    asm volatile("v_and_b32 %0, 31, %1" : "=v"(l32) : "v"(tid));
+    if (SUMI) {  // whatever part of the own-row schedule a short history left undone
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (n_tiles < 2) issue_rows(p.k_self, p.ld_kv);
+        if (n_tiles < 3) {
+            wait_tiles<NPRE>(0);
+            own_k();
+        }
+        if (n_tiles < 4) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            issue_rows(p.v_self, p.ld_kv);
+        }
+        if (n_tiles < 5) {
+            wait_tiles<NPRE>(0);
+            own_v();
+        }
+    }
 
     // ---- SAFE pass (rare): whole workgroup redoes its rows with a running maximum -----------
     float lt[QB];
@@ -523,10 +617,17 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         lt[qb] = st.l[qb] + xhalf(st.l[qb]);
         bad |= !(lt[qb] > kDenomLo && lt[qb] < kDenomHi);
     }
-    if (__syncthreads_or(bad)) {  // also orders the reuse of the LDS ring
+    // Workgroup-wide OR of `bad` through the (idle) landing buffer: one flag per wave in its own
+    // slice, one barrier; the barrier also orders the reuse of the LDS ring below.
+    int *flag_lds = (int *)(lds + kStages * kTileBytes);
+    if (lane == 0) flag_lds[wave * (WQ * 32)] = __builtin_amdgcn_ballot_w64(bad) != 0;
+    __syncthreads();
+    int any_bad = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) any_bad |= flag_lds[w * (WQ * 32)];
+    if (any_bad) {
         prologue();
-        load_q_raw();
-        init_state(std::true_type{});
+        init_safe();
         for (int t = 0; t < n_tiles; ++t) {
             wait_tiles<NPRE>(min(t + kStages - 1, n_tiles) - (t + 1));
             __builtin_amdgcn_s_barrier();
@@ -556,7 +657,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     // A lane holds O^T[32db + 8g + 4hf + 0..3][query]: 8-byte pieces of 32 different rows.  Each
     // wave turns its 32 x 64 block around in its own corner of the (now idle) LDS ring so that
     // the global stores are whole 128-byte rows, 16 bytes per lane.
-    __syncthreads();  // every wave is done reading K/V tiles
+    if (any_bad) __syncthreads();  // SAFE pass: every wave is done reading K/V tiles
     constexpr int kRowPitch = 144;  // 128 B of a row + 16 B pad, keeps 16-byte alignment
     uint8_t *tr = lds + wave * (32 * kRowPitch);
 #pragma unroll
@@ -578,7 +679,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             uint4 val = *(const uint4 *)(tr + r * kRowPitch + cc * 16);
             __bf16 *op = p.o + (row0 + wq) * p.ld_o + h * kDHead + cc * 8;
             if (wq < nq) {
-                *(uint4 *)op = val;
+                __builtin_nontemporal_store(__builtin_bit_cast(u32x4, val), (u32x4 *)op);
             } else if (!SUMI && q0 + wq < Lpad) {
                 *(uint4 *)op = uint4{0, 0, 0, 0};
             }
