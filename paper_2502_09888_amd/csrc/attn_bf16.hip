@@ -27,7 +27,7 @@
 //     This covers logits of any size exactly; it is never taken for unit-scale inputs.
 //   - SUMI: the candidate's own key/value initialise the running state, which is the "+ itself"
 //     term of the mask.
-#include "internal.h"
+#include "attn_common.h"
 
 #include <cstdlib>
 #include <type_traits>
@@ -35,20 +35,11 @@
 namespace climber {
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) uint8_t lds_u8;
-typedef const __attribute__((address_space(1))) uint8_t glb_u8;
+using namespace attn;
 
 constexpr int kTileKeys = 64;                // keys per LDS tile = 2 cache blocks
 constexpr int kTileBytes = 2 * kBlockBytes;  // 16 KiB
 constexpr int kStages = 3;                   // LDS ring of K/V tiles
-constexpr float kSafeSlack = 8.0f;           // SAFE: exp2-domain slack before the row maximum moves
-constexpr float kDenomHi = 1.0e12f;          // FAST is accepted iff kDenomLo < denominator < kDenomHi
-constexpr float kDenomLo = 1.0e-12f;
 
 struct KParams {
     const uint8_t *layer_base;
@@ -63,154 +54,6 @@ struct KParams {
     int uni_cand;          // >= 0: every user has this many candidates (SUMI)
     float scale_log2e;
 };
-
-// Per-wave softmax state for QB blocks of 32 queries.
-template <int QB>
-struct QState {
-    bf16x8 qf[QB][4];  // B operands of S^T: FAST q' = bf16(q*c), SAFE q; [query][16s + 8hf + 0..7]
-    float c[QB];      // qk_scale * log2(e) / tau_row                       (SAFE)
-    float m_ref[QB];  // running reference maximum, raw logit units         (SAFE)
-    float l[QB];      // this half-wave's share of the softmax denominator
-    f32x16 O[2][QB];  // O^T[d block][query block]
-};
-
-struct KFrags { bf16x8 a[4]; };  // K A-operands of a 32-key block (4 k-steps of 16 dims)
-struct VFrags { bf16x8 a[2][2]; };  // V^T A-operands [16-key group][32-dim block]
-
-__device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32, 64); }
-
-// Exchange between the two half-waves: returns max(x, x of the lane 32 away).
-__device__ __forceinline__ float xhalf_max(float x)
-{
-    const unsigned u = __float_as_uint(x);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-
-__device__ __forceinline__ KFrags load_k(const uint8_t *blk, int lane)
-{
-    KFrags f;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) f.a[s] = *(const bf16x8 *)(blk + (s * 64 + lane) * 16);
-    return f;
-}
-
-__device__ __forceinline__ VFrags load_v(const uint8_t *blk, int lane)
-{
-    VFrags f;
-#pragma unroll
-    for (int g = 0; g < 2; ++g)
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-            f.a[g][db] = *(const bf16x8 *)(blk + 4096 + ((g * 2 + db) * 64 + lane) * 16);
-    return f;
-}
-
-// S^T[qb] = K_blk q_qb^T for both query blocks
-template <int QB>
-__device__ __forceinline__ void qk_block(const QState<QB> &st, const KFrags &k, f32x16 (&S)[QB])
-{
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) S[qb][r] = 0.f;
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-            S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k.a[s], st.qf[qb][s], S[qb], 0, 0, 0);
-}
-
-// O^T[db][qb] += V^T_{g,db} P^T
-template <int QB>
-__device__ __forceinline__ void pv_block(QState<QB> &st, const VFrags &v, const bf16x8 (&P)[QB][2])
-{
-#pragma unroll
-    for (int g = 0; g < 2; ++g)
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-                st.O[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v.a[g][db], P[qb][g], st.O[db][qb], 0, 0, 0);
-}
-
-// keys with index >= k_hi are excluded (last blocks of a range only)
-template <int QB>
-__device__ __forceinline__ void mask_block(f32x16 (&S)[QB], int hf, int blk_lo, int k_hi)
-{
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int kidx = blk_lo + 8 * (r >> 2) + 4 * hf + (r & 3);
-        if (kidx >= k_hi) {
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) S[qb][r] = -INFINITY;
-        }
-    }
-}
-
-// p = exp2(S*scale - sub) rounded to bf16 in B-operand order (P[g] holds the keys of 16-key
-// group g); returns the sum of the values before rounding (round-to-nearest is unbiased, so the
-// denominator and the bf16 numerators agree to well below the bf16 rounding of a single term).
-// Plain v_add_f32 on purpose: the v_dot2 family issues into the matrix pipe and would take MFMA
-// slots, whereas adds overlap with the MFMAs of the other wave on the SIMD.
-template <bool AFFINE>
-__device__ __forceinline__ float exp_pack(const f32x16 &S, float scale, float sub, bf16x8 (&P)[2])
-{
-    float sum = 0.f;
-#pragma unroll
-    for (int g = 0; g < 2; ++g)
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(AFFINE ? fmaf(S[8 * g + e], scale, -sub) : S[8 * g + e]);
-            const float p1 = __builtin_amdgcn_exp2f(AFFINE ? fmaf(S[8 * g + e + 1], scale, -sub) : S[8 * g + e + 1]);
-            P[g][e] = (__bf16)p0;
-            P[g][e + 1] = (__bf16)p1;
-            sum += p0 + p1;
-        }
-    return sum;
-}
-
-// FAST softmax of one block: p = exp2(t)
-template <int QB>
-__device__ __forceinline__ void softmax_fast(QState<QB> &st, const f32x16 (&S)[QB], bf16x8 (&P)[QB][2])
-{
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) st.l[qb] += exp_pack<false>(S[qb], 1.f, 0.f, P[qb]);
-}
-
-// SAFE softmax of one block: running maximum in raw logit units, p = exp2((s - m) * c)
-template <int QB>
-__device__ __forceinline__ void softmax_safe(QState<QB> &st, const f32x16 (&S)[QB], bf16x8 (&P)[QB][2])
-{
-    float mx[QB];
-    bool need[QB];
-    bool any = false;
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        float v = fmaxf(S[qb][0], S[qb][1]);
-#pragma unroll
-        for (int r = 2; r < 16; r += 2) v = fmaxf(fmaxf(v, S[qb][r]), S[qb][r + 1]);
-        mx[qb] = xhalf_max(v);  // same in both half-waves
-        need[qb] = (mx[qb] - st.m_ref[qb]) * st.c[qb] > kSafeSlack;
-        any |= need[qb];
-    }
-    if (__builtin_amdgcn_ballot_w64(any) != 0) {
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            const float alpha =
-                need[qb] ? __builtin_amdgcn_exp2f((st.m_ref[qb] - mx[qb]) * st.c[qb]) : 1.f;
-            st.m_ref[qb] = need[qb] ? mx[qb] : st.m_ref[qb];
-            st.l[qb] *= alpha;
-#pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) st.O[db][qb][r] *= alpha;
-        }
-    }
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-        st.l[qb] += exp_pack<true>(S[qb], st.c[qb], st.m_ref[qb] * st.c[qb], P[qb]);
-}
 
 // wait until at most `tiles_in_flight` later tiles (NPRE loads each) are still outstanding
 template <int NPRE>
@@ -313,17 +156,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         for (int i = 0; i < NPRE; ++i)
             __builtin_amdgcn_global_load_lds(src + i * NT * 16, dst + i * NT * 16, 16, 0, 0);
     };
-    // Make tile t readable: wait for this wave's slabs of tile t (later tiles stay in flight),
-    // barrier (every wave's slabs are in LDS, and every wave is past tile t-2, whose buffer is
-    // the one refilled next), then refill.  The barrier is a bare s_barrier: a fence would drain
-    // the loads that are meant to stay in flight.  Called while tile t-1 is still being computed
-    // (the FAST pass prefetches across the tile boundary), hence t-2.
-    auto sync_tile = [&](int t) __attribute__((always_inline)) {
-        wait_tiles<NPRE>(min(t + kStages - 2, n_tiles) - (t + 1));
-        __builtin_amdgcn_s_barrier();
-        if (t + kStages - 2 < n_tiles && t >= 1) issue_tile(t + kStages - 2);
-    };
-
     QState<QB> st;
 
     // FAST start: q' = bf16(q*c) from the raw rows in st.qf, empty state (the candidate's own
@@ -389,7 +221,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         }
     };
     auto prologue = [&]() __attribute__((always_inline)) {
-        // tiles 0 .. kStages-2 in flight; sync_tile(t >= 1) adds tile t + kStages - 2
+        // tiles 0 .. kStages-2 in flight (SAFE pass)
         for (int t = 0; t < kStages - 1 && t < n_tiles; ++t) issue_tile(t);
     };
 

@@ -119,6 +119,17 @@ int check_cache_use(const climber_config *cfg, const climber_kv_cache *cache, in
 // ---- internal entry points used by the stack driver (stack.hip) ---------------------------------
 namespace climber {
 
+// CLIMBER_HIST_FUSED=0 selects the two-kernel history path (cache writer + ring attention) also
+// where the fused kernel applies; for tuning and for testing both.
+static bool fused_history_disabled()
+{
+    static const bool off = [] {
+        const char *e = getenv("CLIMBER_HIST_FUSED");
+        return e && e[0] == '0';
+    }();
+    return off;
+}
+
 int attn_history_strided(const climber_config *cfg, const float *tau_layer, const void *q,
                          const void *k, const void *v, int64_t ld, const int32_t *scen,
                          const int32_t *beh, climber_kv_cache *cache, int32_t layer, void *o,
@@ -126,7 +137,11 @@ int attn_history_strided(const climber_config *cfg, const float *tau_layer, cons
 {
     const CacheView cv = view_of(cache, layer);
     if (cache->rows == 0) return CLIMBER_OK;
-    if (cfg->dtype == CLIMBER_BF16) {
+    // short subsequences, bf16: one kernel writes the cache and attends (K/V rows read once)
+    const bool fused = cfg->dtype == CLIMBER_BF16 && o && !fused_history_disabled() &&
+                       hist_fused_supported(cfg->sub_len, (cfg->flags & CLIMBER_HIST_CAUSAL) != 0);
+    if (fused) {
+    } else if (cfg->dtype == CLIMBER_BF16) {
         int e = rt(launch_kv_write_bf16(cv, k, v, ld, cfg->n_heads, cache->max_pad, s));
         if (e) return e;
     } else {
@@ -146,6 +161,7 @@ int attn_history_strided(const climber_config *cfg, const float *tau_layer, cons
     a.ld_o = ld_o;
     a.max_rows_per_user = cache->max_pad;
     a.total_q_rows = cache->rows;
+    if (fused) return rt(launch_hist_fused_bf16(a, s));
     if (cfg->dtype == CLIMBER_BF16) return rt(launch_attn_hist_bf16(a, s));
     return rt(launch_attn_f32(a, false, cache->rows, s));
 }

@@ -49,6 +49,10 @@ struct AttnArgs {
 // bf16 MFMA flash attention (attn_bf16.hip)
 hipError_t launch_attn_sumi_bf16(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_hist_bf16(const AttnArgs &a, hipStream_t s);
+// fused cache write + attention inside short subsequences (hist_fused_bf16.hip): a.k_self / a.v_self
+// are the history key / value rows (same row stride as the queries)
+bool hist_fused_supported(int sub_len, int causal);
+hipError_t launch_hist_fused_bf16(const AttnArgs &a, hipStream_t s);
 // fp32 reference-path attention (attn_f32.hip); the cache layer holds plain [rows][H][dh] K then V
 hipError_t launch_attn_f32(const AttnArgs &a, bool sumi, int64_t cache_rows, hipStream_t s);
 size_t attn_f32_max_keys();
