@@ -9,7 +9,10 @@ of 64.  One step = the whole path over one batch with all inputs resident in HBM
 the cache, block-diagonal history attention, then SUMI scoring of all 512 candidates per user --
 by default in ONE call (the kernel tiles the candidates internally); `--chunks 4` times the step
 with four sequential calls of 128 candidates per user instead, and that variant is always reported
-in `breakdown` as well.  Prints ONE JSON line (metric = candidates scored per second).
+in `breakdown` as well.  The timed steps rotate over `--sets` (default 3) independent copies of all
+buffers, ~0.5 GB each, so that no step finds its inputs in the 256 MB last-level cache; the same
+loop on one buffer set is reported in `breakdown`.  Prints ONE JSON line (metric = candidates
+scored per second).
 """
 from __future__ import annotations
 
@@ -113,6 +116,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle cpu_baseline leg")
     ap.add_argument("--no-naive", action="store_true", help="skip the naive re-encode baseline")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--sets", type=int, default=3, help="independent buffer sets the timed steps rotate over")
     ap.add_argument("--workload", choices=["attention", "stack"], default="attention",
                     help="attention = configuration 3 (the headline metric); stack = configuration 4, "
                          "the full 4-layer block stack (extra line, same JSON shape)")
@@ -141,45 +145,55 @@ def main():
     cfg = P.Config(n_layers=1, n_heads=H, d_head=dh, n_scen=spec.n_scen, n_beh=spec.n_beh,
                    sub_len=spec.sub_len, dtype=P.BF16, qk_scale=spec.qk_scale)
     bf = torch.bfloat16
-    t_ = {n: torch.from_numpy(w[n]).to(dev).to(bf).contiguous() for n in ("qh", "kh", "vh", "qc", "kc", "vc")}
-    ids = {n: torch.from_numpy(w[n]).to(dev) for n in ("scen", "beh", "cscen", "cbeh")}
-    tau = torch.from_numpy(w["tau"]).to(dev)
     padded = [int(x) for x in np.diff(w["tok_off"])]
-    cache_buf = torch.empty(P.climber_kv_cache_bytes(cfg, padded), dtype=torch.uint8, device=dev)
-    cache = P.climber_kv_cache_create(cfg, [int(x) for x in w["hist_len"]], padded, cache_buf)
-    o_hist = torch.empty((B * L, d), dtype=bf, device=dev)
-
-    # chunked candidate views: chunk c holds candidates [c*Mc, (c+1)*Mc) of every user
-    def make_chunks(n):
-        assert M % n == 0
-        mc = M // n
-        out = []
-        for c in range(n):
-            idx = (torch.arange(B, device=dev)[:, None] * M + c * mc + torch.arange(mc, device=dev)[None, :]).reshape(-1)
-            out.append(dict(q=t_["qc"][idx].contiguous(), k=t_["kc"][idx].contiguous(),
-                            v=t_["vc"][idx].contiguous(), s=ids["cscen"][idx].contiguous(),
-                            b=ids["cbeh"][idx].contiguous(), mc=mc,
-                            off=torch.arange(B + 1, device=dev, dtype=torch.int32) * mc,
-                            o=torch.empty((B * mc, d), dtype=bf, device=dev), idx=idx))
-        return out
-
+    tau = torch.from_numpy(w["tau"]).to(dev)
     nch = args.chunks
     Mc = M // nch
-    chunks = make_chunks(nch)
     other_n = 4 if nch == 1 else 1          # the variant reported beside the timed one
-    other = make_chunks(other_n)
 
-    def encode():
-        P.climber_attn_history(cfg, tau, t_["qh"], t_["kh"], t_["vh"], ids["scen"], ids["beh"],
-                               cache, 0, o_hist)
+    class BufferSet:
+        """One independent copy of every device buffer a step touches."""
 
-    def score_with(chs):
-        for ch in chs:
-            P.climber_attn_sumi(cfg, tau, cache, 0, ch["q"], ch["k"], ch["v"], ch["off"], B * ch["mc"],
-                                ch["mc"], ch["s"], ch["b"], ch["o"])
+        def __init__(self):
+            self.t = {n: torch.from_numpy(w[n]).to(dev).to(bf).contiguous()
+                      for n in ("qh", "kh", "vh", "qc", "kc", "vc")}
+            self.ids = {n: torch.from_numpy(w[n]).to(dev) for n in ("scen", "beh", "cscen", "cbeh")}
+            self.cache_buf = torch.empty(P.climber_kv_cache_bytes(cfg, padded), dtype=torch.uint8, device=dev)
+            self.cache = P.climber_kv_cache_create(cfg, [int(x) for x in w["hist_len"]], padded, self.cache_buf)
+            self.o_hist = torch.empty((B * L, d), dtype=bf, device=dev)
+            self.chunks = self.make_chunks(nch)
 
-    def score():
-        score_with(chunks)
+        # chunked candidate views: chunk c holds candidates [c*Mc, (c+1)*Mc) of every user
+        def make_chunks(self, n):
+            assert M % n == 0
+            mc = M // n
+            out = []
+            for c in range(n):
+                idx = (torch.arange(B, device=dev)[:, None] * M + c * mc + torch.arange(mc, device=dev)[None, :]).reshape(-1)
+                out.append(dict(q=self.t["qc"][idx].contiguous(), k=self.t["kc"][idx].contiguous(),
+                                v=self.t["vc"][idx].contiguous(), s=self.ids["cscen"][idx].contiguous(),
+                                b=self.ids["cbeh"][idx].contiguous(), mc=mc,
+                                off=torch.arange(B + 1, device=dev, dtype=torch.int32) * mc,
+                                o=torch.empty((B * mc, d), dtype=bf, device=dev), idx=idx))
+            return out
+
+        def encode(self):
+            P.climber_attn_history(cfg, tau, self.t["qh"], self.t["kh"], self.t["vh"], self.ids["scen"],
+                                   self.ids["beh"], self.cache, 0, self.o_hist)
+
+        def score_with(self, chs):
+            for ch in chs:
+                P.climber_attn_sumi(cfg, tau, self.cache, 0, ch["q"], ch["k"], ch["v"], ch["off"],
+                                    B * ch["mc"], ch["mc"], ch["s"], ch["b"], ch["o"])
+
+        def score(self):
+            self.score_with(self.chunks)
+
+    sets = [BufferSet() for _ in range(max(1, args.sets))]
+    s0 = sets[0]
+    t_, ids, cache, chunks = s0.t, s0.ids, s0.cache, s0.chunks
+    other = s0.make_chunks(other_n)
+    encode, score, score_with = s0.encode, s0.score, s0.score_with
 
     # one plain device-to-device copy of known size: the kernel the HBM counters of a profile of
     # this command are calibrated against (not part of the timed region)
@@ -187,24 +201,40 @@ def main():
     calib_dst = torch.empty_like(calib_src)
     calib_dst.copy_(calib_src)
 
-    for _ in range(args.warmup):
-        encode()
-        score()
-    torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        encode()
-        ev[i][0].record()
-        score()
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    sumi_ms = float(np.mean([a.elapsed_time(b) for a, b in ev])) / nch   # avg SUMI launch
+    def run_steps(use_sets, n):
+        """n steps rotating over use_sets; returns (ms per step, mean ms of a scoring launch)."""
+        for i in range(args.warmup):
+            use_sets[i % len(use_sets)].encode()
+            use_sets[i % len(use_sets)].score()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        t0 = time.perf_counter()
+        for i in range(n):
+            bs = use_sets[i % len(use_sets)]
+            bs.encode()
+            ev[i][0].record()
+            bs.score()
+            ev[i][1].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / n, float(np.mean([a.elapsed_time(b) for a, b in ev])) / nch
+
+    ms_per_step, sumi_ms = run_steps(sets, args.steps)            # the timed region of the metric
+    ms_one_set, sumi_ms_one_set = run_steps(sets[:1], args.steps)
     cands = B * M
     value = cands / (ms_per_step * 1e-3)
+
+    # MFMA-only probe: the bf16 matrix rate the device sustains at its own clocks
+    probe_sink = torch.empty(2048 * 256, dtype=torch.float32, device=dev)
+    P.climber_probe_mfma(2048, 200, probe_sink)
+    torch.cuda.synchronize()
+    pa, pb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    pa.record()
+    for _ in range(5):
+        P.climber_probe_mfma(2048, 4000, probe_sink)
+    pb.record()
+    torch.cuda.synchronize()
+    mfma_probe_tflops = 5 * 2048 * 4 * 4000 * 4 * 32768.0 / (pa.elapsed_time(pb) * 1e-3) / 1e12
 
     # algorithmic work of one SUMI launch: 4 * (L+1) * dh flop per (candidate, head)
     flop_launch = 4.0 * (L + 1) * dh * H * B * Mc
@@ -255,8 +285,13 @@ def main():
                      "traffic": measured_traffic(), "launch_ms": sumi_ms, "flop_per_launch": flop_launch,
                      "algorithmic_bytes_per_launch": kv_bytes + qkvo_bytes,
                      "algorithmic_GBps": (kv_bytes + qkvo_bytes) / (sumi_ms * 1e-3) / 1e9,
-                     "hbm_peak_GBps": PEAK_HBM_GBS},
-        "breakdown": {"encode_ms": encode_ms, "score_ms": score_ms,
+                     "hbm_peak_GBps": PEAK_HBM_GBS,
+                     "mfma_only_probe_TFLOPs": mfma_probe_tflops,
+                     "frac_of_mfma_only_probe": achieved / mfma_probe_tflops},
+        "breakdown": {"buffer_sets_rotated": len(sets),
+                      "single_buffer_set": {"ms_per_step": ms_one_set, "candidates_per_s": cands / (ms_one_set * 1e-3),
+                                            "scoring_launch_ms": sumi_ms_one_set},
+                      "encode_ms": encode_ms, "score_ms": score_ms,
                       "score_only_candidates_per_s": cands / (score_ms * 1e-3),
                       "other_variant": {"chunks": other_n, "candidates_per_call_per_user": M // other_n,
                                         "score_ms": other_ms,

@@ -75,6 +75,8 @@ def load_library():
     lib.climber_attn_history.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.climber_attn_sumi.restype = C.c_int
     lib.climber_attn_sumi.argtypes = [cfgp, vp, vp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.climber_probe_mfma.restype = C.c_int
+    lib.climber_probe_mfma.argtypes = [i32, i32, vp, vp]
     lib.climber_workspace_bytes.restype = sz
     lib.climber_workspace_bytes.argtypes = [cfgp, i64]
     lib.climber_layer_forward.restype = C.c_int
@@ -176,6 +178,12 @@ def climber_attn_sumi(cfg: Config, tau_layer, cache: KVCache, layer: int, q_c, k
                                          _ptr(q_c), _ptr(k_c), _ptr(v_c), _ptr(cand_off), m_total,
                                          m_max, _ptr(cand_scen), _ptr(cand_beh), _ptr(o_c),
                                          _stream(stream)), "climber_attn_sumi")
+
+
+def climber_probe_mfma(workgroups: int, iters: int, sink, stream=None) -> None:
+    """MFMA-only probe launch (measurement aid); sink: float32 device tensor of workgroups*256."""
+    _ok(load_library().climber_probe_mfma(workgroups, iters, _ptr(sink), _stream(stream)),
+        "climber_probe_mfma")
 
 
 def climber_workspace_bytes(cfg: Config, max_rows: int) -> int:

@@ -130,3 +130,22 @@ def test_full_size_sampled_users(spec, users):
     e = max_abs(oh[t0:t0 + Lb], ref[:Lb])
     say(f"  user {b}: history max-abs {e:.3e}")
     assert e < 2e-2
+
+
+def test_two_kernel_history_path():
+    # Subsequences of 128 / 256 tokens take the fused cache-write + attention kernel by default; the
+    # same cases must also hold on the two-kernel path (cache writer, then ring attention), which
+    # the library reads from the environment once per process: run them in a child process.
+    import os
+    import subprocess
+    import sys
+    if os.environ.get("CLIMBER_HIST_FUSED") == "0":
+        pytest.skip("this is the child process")
+    env = dict(os.environ, CLIMBER_HIST_FUSED="0")
+    here = os.path.dirname(os.path.abspath(__file__))
+    r = subprocess.run([sys.executable, "-u", "-m", "pytest", os.path.join(here, "test_gpu_attention.py"),
+                        "-m", "gpu", "-x", "-q", "-k", "ragged or small_multi or large_logits",
+                        "--timeout", "120", "--timeout-method", "thread"],
+                       env=env, capture_output=True, text=True, timeout=600)
+    say(r.stdout[-1500:])
+    assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-2000:]
