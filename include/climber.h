@@ -206,12 +206,13 @@ int climber_sumi_score(const climber_config *cfg, const climber_weights *weights
 
 /* Measurement aid, not a step of the method: launches `workgroups` workgroups of 4 waves, each wave
  * issuing iters x 4 independent v_mfma_f32_32x32x16_bf16 (2*32*32*16 FLOP each) on register
- * operands and nothing else, so that a caller timing the launch obtains the bf16 MFMA rate the
+ * operands (pseudo-random values of unit scale, rotating, so that the operand bits toggle the way
+ * they do for real activations: the clock the device sustains depends on that) and nothing else, so that a caller timing the launch obtains the bf16 MFMA rate the
  * device sustains at its own clocks: workgroups*4*iters*4*32768 FLOP per launch.  The roofline of
  * the attention kernels (Eq. (3): S = Q K^T and A V are dense contractions) is quoted against the
  * datasheet peak; this figure says how much of that peak the clocks allow.  sink: device buffer of
  * workgroups*256 floats that receives one value per thread.  Errors: CLIMBER_ERR_NULL,
- * CLIMBER_ERR_SHAPE (workgroups or iters < 1, workgroups > 65536), CLIMBER_ERR_RUNTIME. */
+ * CLIMBER_ERR_SHAPE (workgroups < 1 or > 65536, iters < 4 or not a multiple of 4), CLIMBER_ERR_RUNTIME. */
 int climber_probe_mfma(int32_t workgroups, int32_t iters, float *sink, void *stream);
 
 #ifdef __cplusplus
