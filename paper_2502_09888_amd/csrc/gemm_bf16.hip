@@ -19,6 +19,7 @@
 //   2 x 2 (macro tile 128 x 128): for problems too small to fill the chip with larger tiles.
 #include "gemm.h"
 
+#include <algorithm>
 #include <cstdlib>
 
 namespace climber {
@@ -31,20 +32,33 @@ typedef const __attribute__((address_space(1))) uint8_t glb_u8;
 
 constexpr int BK = 32;      // k-tile
 
-__global__ __launch_bounds__(256) void pack_weight_kernel(const __bf16 *w, __bf16 *out, int K, int N)
+__device__ __forceinline__ void pack_chunk(const __bf16 *w, __bf16 *out, int K, int N, int64_t chunk)
 {
     // one thread per 16-byte chunk (nb, ks, lane)
-    const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t n_chunks = (int64_t)(N / 32) * (K / 16) * 64;
-    if (chunk >= n_chunks) return;
     const int lane = (int)(chunk & 63);
     const int64_t t = chunk >> 6;
     const int ks = (int)(t % (K / 16)), nb = (int)(t / (K / 16));
     const int n = 32 * nb + (lane & 31), k0 = 16 * ks + 8 * (lane >> 5);
-    __attribute__((aligned(16))) __bf16 v[8];
+    bf16x8 v;
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = w[(int64_t)(k0 + e) * N + n];
-    ((uint4 *)out)[chunk] = *(const uint4 *)v;
+    ((bf16x8 *)out)[chunk] = v;
+}
+
+__global__ __launch_bounds__(256) void pack_weight_kernel(const __bf16 *w, __bf16 *out, int K, int N)
+{
+    const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (chunk < (int64_t)(N / 32) * (K / 16) * 64) pack_chunk(w, out, K, N, chunk);
+}
+
+// blockIdx.y = job
+__global__ __launch_bounds__(256) void pack_weights_kernel(const PackJobs jobs)
+{
+    const int j = blockIdx.y, K = jobs.K[j], N = jobs.N[j];
+    const int64_t n_chunks = (int64_t)(N / 32) * (K / 16) * 64;
+    for (int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x; chunk < n_chunks;
+         chunk += (int64_t)gridDim.x * 256)
+        pack_chunk((const __bf16 *)jobs.w[j], (__bf16 *)jobs.packed[j], K, N, chunk);
 }
 
 // exact-erf GELU, erf by the rational/exponential formula 7.1.26 of Abramowitz & Stegun
@@ -251,6 +265,18 @@ hipError_t pack_weight(const void *w, void *packed, int K, int N, hipStream_t s)
     const int64_t n_chunks = (int64_t)(N / 32) * (K / 16) * 64;
     hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, s,
                        (const __bf16 *)w, (__bf16 *)packed, K, N);
+    return hipGetLastError();
+}
+
+hipError_t pack_weights(const PackJobs &jobs, hipStream_t s)
+{
+    if (jobs.n <= 0) return hipSuccess;
+    if (jobs.n > kMaxPackJobs) return hipErrorInvalidValue;
+    int64_t most = 0;
+    for (int j = 0; j < jobs.n; ++j)
+        most = std::max<int64_t>(most, (int64_t)(jobs.N[j] / 32) * (jobs.K[j] / 16) * 64);
+    const unsigned gx = (unsigned)std::min<int64_t>((most + 255) / 256, 1024);
+    hipLaunchKernelGGL(pack_weights_kernel, dim3(gx, (unsigned)jobs.n), dim3(256), 0, s, jobs);
     return hipGetLastError();
 }
 

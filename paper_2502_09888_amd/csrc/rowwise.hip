@@ -1,9 +1,11 @@
-// Row-wise kernels of the layer stack: RMSNorm (fp32 residual stream -> bf16 GEMM operand) and the
-// bf16 -> fp32 widening of the input embeddings.
+// Row-wise kernels of the layer stack: RMSNorm (fp32 residual stream -> bf16 GEMM operand), also
+// straight from the bf16 input embeddings (which it widens into the fp32 stream on the way).
 #include "gemm.h"
 
 namespace climber {
 namespace {
+
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 
 // one wavefront per row
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *x, const __bf16 *g, __bf16 *y,
@@ -32,15 +34,30 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *x, const __bf
     }
 }
 
-__global__ __launch_bounds__(256) void cast_kernel(const __bf16 *x, float *y, int64_t n8)
+// the same for bf16 input rows, which are also widened into the fp32 residual stream
+__global__ __launch_bounds__(256) void rmsnorm_bf16_kernel(const __bf16 *x, const __bf16 *g, __bf16 *y,
+                                                           float *x32, int64_t rows, int d, float eps)
 {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
-        const uint4 raw = ((const uint4 *)x)[i];
-        const __bf16 *b = (const __bf16 *)&raw;
-        float4 lo = {(float)b[0], (float)b[1], (float)b[2], (float)b[3]};
-        float4 hi = {(float)b[4], (float)b[5], (float)b[6], (float)b[7]};
-        ((float4 *)y)[2 * i] = lo;
-        ((float4 *)y)[2 * i + 1] = hi;
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const __bf16 *xr = x + row * d;
+    float ss = 0.f;
+    for (int e = lane * 4; e < d; e += 256) {
+        const bf16x4 v = *(const bf16x4 *)(xr + e);
+        const float4 f = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+        ss += f.x * f.x + f.y * f.y + f.z * f.z + f.w * f.w;
+        *(float4 *)(x32 + row * d + e) = f;
+    }
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    const float r = 1.f / sqrtf(ss / (float)d + eps);
+    __bf16 *yr = y + row * d;
+    for (int e = lane * 4; e < d; e += 256) {
+        const bf16x4 v = *(const bf16x4 *)(xr + e);
+        bf16x4 out;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = (__bf16)((float)v[i] * r * (float)g[e + i]);
+        *(bf16x4 *)(yr + e) = out;
     }
 }
 
@@ -56,13 +73,13 @@ hipError_t rmsnorm_to_bf16(const float *x, const void *g, void *y, int64_t rows,
     return hipGetLastError();
 }
 
-hipError_t cast_bf16_to_f32(const void *x, float *y, int64_t n, hipStream_t s)
+hipError_t rmsnorm_from_bf16(const void *x, const void *g, void *y, float *x32, int64_t rows, int d,
+                             float eps, hipStream_t s)
 {
-    if (n <= 0) return hipSuccess;
-    if (n % 8 != 0) return hipErrorInvalidValue;
-    const int64_t n8 = n / 8, blocks = (n8 + 255) / 256;
-    hipLaunchKernelGGL(cast_kernel, dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, s,
-                       (const __bf16 *)x, y, n8);
+    if (rows <= 0) return hipSuccess;
+    if (d % 4 != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rmsnorm_bf16_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
+                       (const __bf16 *)x, (const __bf16 *)g, (__bf16 *)y, x32, rows, d, eps);
     return hipGetLastError();
 }
 

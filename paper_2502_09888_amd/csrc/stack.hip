@@ -23,9 +23,12 @@ struct Workspace {
     uint8_t *qkv;   // [rows][3d]  bf16 fused projection output
     uint8_t *o;     // [rows][d]   bf16 attention output
     uint8_t *u;     // [rows][F]   bf16 FFN hidden
-    uint8_t *wpack; // packed weight of the GEMM in flight (largest of the four)
+    uint8_t *wpack; // packed weights of every layer: [layer]{wqkv, wo, w1, w2}
+    size_t wlayer;  // bytes of one layer's packed weights
     size_t total;
 };
+
+struct PackedLayer { const uint8_t *wqkv, *wo, *w1, *w2; };
 
 Workspace carve(const climber_config *c, int64_t rows, void *base)
 {
@@ -40,10 +43,17 @@ Workspace carve(const climber_config *c, int64_t rows, void *base)
     w.qkv = take(n * 3 * d * 2);
     w.o = take(n * d * 2);
     w.u = take(n * F * 2);
-    const size_t wmax = std::max((size_t)3 * d * d, d * F) * 2;
-    w.wpack = take(wmax);
+    w.wlayer = up256((4 * d * d + 2 * d * F) * 2);
+    w.wpack = take(w.wlayer * (size_t)std::max(c->n_layers, 1));
     w.total = off;
     return w;
+}
+
+PackedLayer packed_layer(const climber_config *c, const Workspace &ws, int slot)
+{
+    const size_t d = c->d_model, F = c->d_ffn;
+    const uint8_t *b = ws.wpack + ws.wlayer * (size_t)slot;
+    return PackedLayer{b, b + 3 * d * d * 2, b + 4 * d * d * 2, b + (4 * d * d + d * F) * 2};
 }
 
 int check_stack_config(const climber_config *c)
@@ -64,16 +74,48 @@ int rt(hipError_t e) { return e == hipSuccess ? CLIMBER_OK : CLIMBER_ERR_RUNTIME
         if (e_) return e_; \
     } while (0)
 
-// one layer on `rows` rows; ws.x32 is not touched here
-int run_layer(const climber_config *cfg, const climber_layer_weights *w, const float *tau_layer,
-              int32_t layer, int32_t mode, climber_kv_cache *cache, const float *x_in, float *x_out,
-              const int32_t *scen, const int32_t *beh, const int32_t *cand_off, int32_t m_total,
-              int32_t m_max, int64_t rows, const Workspace &ws, hipStream_t s)
+// MFMA fragment order for the weights of layers [0, n) into slots [0, n) of the workspace: one
+// launch per four layers
+int pack_layers(const climber_config *cfg, const climber_layer_weights *layers, int n,
+                const Workspace &ws, hipStream_t s)
+{
+    const int d = cfg->d_model, F = cfg->d_ffn;
+    PackJobs jobs;
+    jobs.n = 0;
+    for (int l = 0; l < n; ++l) {
+        const PackedLayer pl = packed_layer(cfg, ws, l);
+        const void *src[4] = {layers[l].wqkv, layers[l].wo, layers[l].w1, layers[l].w2};
+        const uint8_t *dst[4] = {pl.wqkv, pl.wo, pl.w1, pl.w2};
+        const int K[4] = {d, d, d, F}, N[4] = {3 * d, d, F, d};
+        for (int i = 0; i < 4; ++i) {
+            jobs.w[jobs.n] = src[i];
+            jobs.packed[jobs.n] = const_cast<uint8_t *>(dst[i]);
+            jobs.K[jobs.n] = K[i];
+            jobs.N[jobs.n] = N[i];
+            ++jobs.n;
+        }
+        if (jobs.n == kMaxPackJobs || l + 1 == n) {
+            TRY(rt(pack_weights(jobs, s)));
+            jobs.n = 0;
+        }
+    }
+    return CLIMBER_OK;
+}
+
+// one layer on `rows` rows.  The input rows are either the fp32 stream x_in or, for the first layer
+// of a stack call, the bf16 embeddings x_in_bf16, which are widened into x_in on the way.
+int run_layer(const climber_config *cfg, const climber_layer_weights *w, const PackedLayer &pw,
+              const float *tau_layer, int32_t layer, int32_t mode, climber_kv_cache *cache,
+              const void *x_in_bf16, float *x_in, float *x_out, const int32_t *scen, const int32_t *beh,
+              const int32_t *cand_off, int32_t m_total, int32_t m_max, int64_t rows, const Workspace &ws,
+              hipStream_t s)
 {
     const int d = cfg->d_model, F = cfg->d_ffn, M = (int)rows;
-    TRY(rt(rmsnorm_to_bf16(x_in, w->g1, ws.xn, rows, d, cfg->rms_eps, s)));
-    TRY(rt(pack_weight(w->wqkv, ws.wpack, d, 3 * d, s)));
-    TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xn, d, ws.wpack, M, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, s)));
+    if (x_in_bf16)
+        TRY(rt(rmsnorm_from_bf16(x_in_bf16, w->g1, ws.xn, x_in, rows, d, cfg->rms_eps, s)));
+    else
+        TRY(rt(rmsnorm_to_bf16(x_in, w->g1, ws.xn, rows, d, cfg->rms_eps, s)));
+    TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xn, d, pw.wqkv, M, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, s)));
     const uint8_t *q = ws.qkv, *k = ws.qkv + (size_t)d * 2, *v = ws.qkv + (size_t)2 * d * 2;
     if (mode == CLIMBER_MODE_HISTORY) {
         TRY(attn_history_strided(cfg, tau_layer, q, k, v, 3 * d, scen, beh, cache, layer,
@@ -83,13 +125,10 @@ int run_layer(const climber_config *cfg, const climber_layer_weights *w, const f
         TRY(attn_sumi_strided(cfg, tau_layer, cache, layer, q, k, v, 3 * d, cand_off, m_total, m_max,
                               scen, beh, ws.o, d, s));
     }
-    TRY(rt(pack_weight(w->wo, ws.wpack, d, d, s)));
-    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o, d, ws.wpack, M, d, d, ws.h32, d, x_in, d, s)));
+    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o, d, pw.wo, M, d, d, ws.h32, d, x_in, d, s)));
     TRY(rt(rmsnorm_to_bf16(ws.h32, w->g2, ws.xn, rows, d, cfg->rms_eps, s)));
-    TRY(rt(pack_weight(w->w1, ws.wpack, d, F, s)));
-    TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xn, d, ws.wpack, M, F, d, ws.u, F, nullptr, 0, s)));
-    TRY(rt(pack_weight(w->w2, ws.wpack, F, d, s)));
-    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.u, F, ws.wpack, M, d, F, x_out, d, ws.h32, d, s)));
+    TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xn, d, pw.w1, M, F, d, ws.u, F, nullptr, 0, s)));
+    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.u, F, pw.w2, M, d, F, x_out, d, ws.h32, d, s)));
     return CLIMBER_OK;
 }
 
@@ -146,8 +185,10 @@ int climber_layer_forward(const climber_config *cfg, const climber_layer_weights
     const Workspace ws = carve(cfg, rows, workspace);
     if (ws_bytes < ws.total) return CLIMBER_ERR_BUFSIZE;
     if (rows == 0) return CLIMBER_OK;
-    return run_layer(cfg, w, tau_layer, layer, mode, cache, x_in, x_out, scen, beh, cand_off, m_total,
-                     m_max, rows, ws, (hipStream_t)stream);
+    hipStream_t s = (hipStream_t)stream;
+    TRY(pack_layers(cfg, w, 1, ws, s));
+    return run_layer(cfg, w, packed_layer(cfg, ws, 0), tau_layer, layer, mode, cache, nullptr,
+                     const_cast<float *>(x_in), x_out, scen, beh, cand_off, m_total, m_max, rows, ws, s);
 }
 
 int climber_history_encode(const climber_config *cfg, const climber_weights *weights,
@@ -169,11 +210,12 @@ int climber_history_encode(const climber_config *cfg, const climber_weights *wei
     if (ws_bytes < ws.total) return CLIMBER_ERR_BUFSIZE;
     if (rows == 0) return CLIMBER_OK;
     hipStream_t s = (hipStream_t)stream;
-    TRY(rt(cast_bf16_to_f32(x_hist, ws.x32, rows * cfg->d_model, s)));
+    TRY(pack_layers(cfg, weights->layers, cfg->n_layers, ws, s));
     const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
     for (int l = 0; l < cfg->n_layers; ++l) {
         const bool last = l + 1 == cfg->n_layers;  // nothing reads the last layer's history output
-        TRY(run_layer(cfg, &weights->layers[l], tau + l * tl, l, CLIMBER_MODE_HISTORY, cache, ws.x32,
+        TRY(run_layer(cfg, &weights->layers[l], packed_layer(cfg, ws, l), tau + l * tl, l,
+                      CLIMBER_MODE_HISTORY, cache, l == 0 ? x_hist : nullptr, ws.x32,
                       last ? nullptr : ws.x32, scen, beh, nullptr, 0, 0, rows, ws, s));
     }
     return CLIMBER_OK;
@@ -199,14 +241,15 @@ int climber_sumi_score(const climber_config *cfg, const climber_weights *weights
     if (ws_bytes < ws.total) return CLIMBER_ERR_BUFSIZE;
     if (m_total == 0) return CLIMBER_OK;
     hipStream_t s = (hipStream_t)stream;
-    TRY(rt(cast_bf16_to_f32(x_cand, ws.x32, (int64_t)m_total * cfg->d_model, s)));
+    TRY(pack_layers(cfg, weights->layers, cfg->n_layers, ws, s));
     const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
     for (int l = 0; l < cfg->n_layers; ++l) {
         const bool last = l + 1 == cfg->n_layers;
         // the cache is only read in candidate mode
-        TRY(run_layer(cfg, &weights->layers[l], tau + l * tl, l, CLIMBER_MODE_CANDIDATE,
-                      const_cast<climber_kv_cache *>(cache), ws.x32, last ? y_cand : ws.x32,
-                      cand_scen, cand_beh, cand_off, m_total, m_max, m_total, ws, s));
+        TRY(run_layer(cfg, &weights->layers[l], packed_layer(cfg, ws, l), tau + l * tl, l,
+                      CLIMBER_MODE_CANDIDATE, const_cast<climber_kv_cache *>(cache),
+                      l == 0 ? x_cand : nullptr, ws.x32, last ? y_cand : ws.x32, cand_scen, cand_beh,
+                      cand_off, m_total, m_max, m_total, ws, s));
     }
     return CLIMBER_OK;
 }
