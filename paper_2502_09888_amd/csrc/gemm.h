@@ -7,6 +7,22 @@ namespace climber {
 
 enum { EPI_STORE_BF16 = 0, EPI_GELU_BF16 = 1, EPI_RESID_F32 = 2 };
 
+// RMSNorm folded into the projections around it.  A projection whose input is RMSNorm(x; g) runs on
+// the plain bf16 rows of x with the gain folded into the weight rows (pack job with `gain`) and
+// multiplies every output row by r = 1/sqrt(mean(x^2) + eps) in its epilogue (`in_norm`).  The
+// projection that produces x (EPI_RESID_F32) writes, besides the fp32 rows, their bf16 copy and
+// the sums of squares of its 64-column slices (`out_norm`); d/64 partial sums per row.
+struct RowNormIn {          // consumer side; ss == nullptr: no scaling
+    const float *ss;        // [rows][n_part] partial sums of squares of the input rows
+    int n_part;
+    float inv_d, eps;
+};
+struct RowNormOut {         // producer side; ss == nullptr: fp32 rows only
+    float *ss;              // [rows][N/64]
+    void *xb;               // bf16 copy of the output rows, [rows][ldb]
+    int64_t ldb;
+};
+
 // W [K][N] bf16 row-major -> MFMA B-operand fragments (same byte size).  K % 16 == 0, N % 32 == 0.
 hipError_t pack_weight(const void *w, void *packed, int K, int N, hipStream_t s);
 
@@ -14,6 +30,7 @@ hipError_t pack_weight(const void *w, void *packed, int K, int N, hipStream_t s)
 constexpr int kMaxPackJobs = 16;
 struct PackJobs {
     const void *w[kMaxPackJobs];
+    const void *gain[kMaxPackJobs];  // bf16 [K] multiplied into the rows of w, or nullptr
     void *packed[kMaxPackJobs];
     int K[kMaxPackJobs], N[kMaxPackJobs];
     int n;
@@ -23,13 +40,14 @@ hipError_t pack_weights(const PackJobs &jobs, hipStream_t s);
 // C = A W (+ epilogue).  A: bf16 [M][lda]; w_packed from pack_weight; N % 128 == 0, K % 64 == 0.
 // EPI_STORE_BF16 / EPI_GELU_BF16: C is bf16 [M][ldc].  EPI_RESID_F32: C is fp32, C = acc + resid.
 hipError_t gemm_bf16(int epi, const void *A, int64_t lda, const void *w_packed, int M, int N, int K,
-                     void *C, int64_t ldc, const float *resid, int64_t ldr, hipStream_t s);
+                     void *C, int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &in_norm,
+                     const RowNormOut &out_norm, hipStream_t s);
 
-// y[r][:] = bf16( x[r][:] / sqrt(mean(x[r]^2) + eps) * g[:] ),  x fp32 [rows][d], g bf16 [d]
-hipError_t rmsnorm_to_bf16(const float *x, const void *g, void *y, int64_t rows, int d, float eps,
-                           hipStream_t s);
-// the same from bf16 rows, which are also widened into the fp32 residual stream x32 (first layer)
-hipError_t rmsnorm_from_bf16(const void *x, const void *g, void *y, float *x32, int64_t rows, int d,
-                             float eps, hipStream_t s);
+// What the first projection of a stack call needs of its input rows: the sum of squares of every
+// row into ss[row][0] (ss[row][1 .. n_part-1] = 0) and
+//   from bf16 rows x (the embeddings): the fp32 copy x32 (the residual stream);
+//   from fp32 rows x: the bf16 copy xb.
+hipError_t row_prep_bf16(const void *x, float *x32, float *ss, int n_part, int64_t rows, int d, hipStream_t s);
+hipError_t row_prep_f32(const float *x, void *xb, float *ss, int n_part, int64_t rows, int d, hipStream_t s);
 
 }  // namespace climber

@@ -21,18 +21,21 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 namespace climber {
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 typedef const __attribute__((address_space(1))) uint8_t glb_u8;
 
 constexpr int BK = 32;      // k-tile
 
-__device__ __forceinline__ void pack_chunk(const __bf16 *w, __bf16 *out, int K, int N, int64_t chunk)
+__device__ __forceinline__ void pack_chunk(const __bf16 *w, const __bf16 *gain, __bf16 *out, int K, int N,
+                                           int64_t chunk)
 {
     // one thread per 16-byte chunk (nb, ks, lane)
     const int lane = (int)(chunk & 63);
@@ -41,14 +44,17 @@ __device__ __forceinline__ void pack_chunk(const __bf16 *w, __bf16 *out, int K, 
     const int n = 32 * nb + (lane & 31), k0 = 16 * ks + 8 * (lane >> 5);
     bf16x8 v;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = w[(int64_t)(k0 + e) * N + n];
+    for (int e = 0; e < 8; ++e) {
+        const __bf16 x = w[(int64_t)(k0 + e) * N + n];
+        v[e] = gain ? (__bf16)((float)x * (float)gain[k0 + e]) : x;
+    }
     ((bf16x8 *)out)[chunk] = v;
 }
 
 __global__ __launch_bounds__(256) void pack_weight_kernel(const __bf16 *w, __bf16 *out, int K, int N)
 {
     const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (chunk < (int64_t)(N / 32) * (K / 16) * 64) pack_chunk(w, out, K, N, chunk);
+    if (chunk < (int64_t)(N / 32) * (K / 16) * 64) pack_chunk(w, nullptr, out, K, N, chunk);
 }
 
 // blockIdx.y = job
@@ -58,7 +64,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const PackJobs jobs)
     const int64_t n_chunks = (int64_t)(N / 32) * (K / 16) * 64;
     for (int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x; chunk < n_chunks;
          chunk += (int64_t)gridDim.x * 256)
-        pack_chunk((const __bf16 *)jobs.w[j], (__bf16 *)jobs.packed[j], K, N, chunk);
+        pack_chunk((const __bf16 *)jobs.w[j], (const __bf16 *)jobs.gain[j], (__bf16 *)jobs.packed[j], K, N, chunk);
 }
 
 // exact-erf GELU, erf by the rational/exponential formula 7.1.26 of Abramowitz & Stegun
@@ -75,6 +81,19 @@ __device__ __forceinline__ float gelu_erf(float x)
     const float erf_abs = 1.f - poly * t * e;
     const float erf_x = x < 0.f ? -erf_abs : erf_abs;
     return 0.5f * x * (1.f + erf_x);
+}
+
+// sum over the 16 lanes of a DPP row, in every lane of the row (cross-lane adds on the VALU)
+__device__ __forceinline__ float row_sum16(float x)
+{
+    auto dpp = [](float v, auto ctrl) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xf, 0xf, false));
+    };
+    x += dpp(x, std::integral_constant<int, 0xB1>{});   // quad_perm [1,0,3,2]
+    x += dpp(x, std::integral_constant<int, 0x4E>{});   // quad_perm [2,3,0,1]
+    x += dpp(x, std::integral_constant<int, 0x141>{});  // row_half_mirror
+    x += dpp(x, std::integral_constant<int, 0x140>{});  // row_mirror
+    return x;
 }
 
 template <int N>
@@ -94,7 +113,7 @@ __device__ __forceinline__ void wait_vm()
 template <int EPI, int WM, int WN, int kStages>
 __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
     const __bf16 *A, int64_t lda, const __bf16 *Wp, int M, int N, int K, void *C, int64_t ldc,
-    const float *resid, int64_t ldr)
+    const float *resid, int64_t ldr, const RowNormIn nin, const RowNormOut nout)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr int kABytes = BM * BK * 2, kBBytes = BN * BK * 2, kStageBytes = kABytes + kBBytes;
@@ -143,6 +162,22 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // Input rows that were not normalised: r = 1/sqrt(mean(x^2) + eps) of row 32i + l32 scales the
+    // whole output row (a lane's accumulators of block row i all belong to that one row).  The
+    // partial sums of squares are requested here, ahead of the k-loop, and first touched in the
+    // epilogue, so nothing waits for them (8 partial sums per row, d_model = 512, is the fast path).
+    constexpr bool SCALED = EPI != EPI_RESID_F32;
+    float4 raw_ss[SCALED ? WM : 1][2];
+    const bool ss8 = SCALED && nin.ss && nin.n_part == 8;
+    if (ss8) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            const int row = min(m0 + 32 * (WM * wm + i) + l32, M - 1);
+            raw_ss[i][0] = *(const float4 *)(nin.ss + (int64_t)row * 8);
+            raw_ss[i][1] = *(const float4 *)(nin.ss + (int64_t)row * 8 + 4);
+        }
+    }
+
     for (int kt = 0; kt < kStages - 1 && kt < n_kt; ++kt) issue(kt);
     for (int kt = 0; kt < n_kt; ++kt) {
         // tiles kt+1 .. kt+kStages-2 may stay in flight
@@ -179,6 +214,24 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
     // corner of the (now idle) LDS ring and stores whole rows, 16 bytes per lane.
     __syncthreads();  // every wave is done reading the last k-tile
     constexpr bool F32 = EPI == EPI_RESID_F32;
+    float rs[WM];
+#pragma unroll
+    for (int i = 0; i < WM; ++i) rs[i] = 1.f;
+    if (SCALED && nin.ss) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            float ss = 0.f;
+            if (ss8) {
+                const float4 u = raw_ss[i][0], v = raw_ss[i][1];
+                ss = ((u.x + u.y) + (u.z + u.w)) + ((v.x + v.y) + (v.z + v.w));
+            } else {
+                const int row = min(m0 + 32 * (WM * wm + i) + l32, M - 1);
+                for (int q = 0; q < nin.n_part; ++q) ss += nin.ss[(int64_t)row * nin.n_part + q];
+            }
+            rs[i] = 1.f / sqrtf(ss * nin.inv_d + nin.eps);
+        }
+    }
+
     constexpr int CW = WN * 32;                       // columns of a wave's block
     constexpr int kElem = F32 ? 4 : 2;
     constexpr int kPitch = CW * kElem + 16;           // bytes per staged row
@@ -198,7 +251,7 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
                     __attribute__((aligned(8))) __bf16 v[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float x = acc[i][j][4 * g + e];
+                        const float x = acc[i][j][4 * g + e] * rs[i];
                         v[e] = (__bf16)(EPI == EPI_GELU_BF16 ? gelu_erf(x) : x);
                     }
                     *(uint2 *)(tr + l32 * kPitch + col * 2) = *(const uint2 *)v;
@@ -211,16 +264,29 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
             const int id = it * 64 + lane, r = id / kChunksPerRow, cc = id % kChunksPerRow;
             const int row = row_base + r;
             uint4 val = *(const uint4 *)(tr + r * kPitch + cc * 16);
+            float sq = 0.f;
             if (row < M) {
                 if (F32) {
                     const int col = col_base + cc * 4;
-                    const float4 rs = *(const float4 *)(resid + (int64_t)row * ldr + col);
+                    const float4 rsd = *(const float4 *)(resid + (int64_t)row * ldr + col);
                     float4 o = *(const float4 *)&val;
-                    o.x += rs.x; o.y += rs.y; o.z += rs.z; o.w += rs.w;
+                    o.x += rsd.x; o.y += rsd.y; o.z += rsd.z; o.w += rsd.w;
                     *(float4 *)((float *)C + (int64_t)row * ldc + col) = o;
+                    if (nout.ss) {
+                        bf16x4 ob;
+                        ob[0] = (__bf16)o.x; ob[1] = (__bf16)o.y; ob[2] = (__bf16)o.z; ob[3] = (__bf16)o.w;
+                        *(bf16x4 *)((__bf16 *)nout.xb + (int64_t)row * nout.ldb + col) = ob;
+                    }
+                    sq = o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
                 } else {
                     *(uint4 *)((__bf16 *)C + (int64_t)row * ldc + col_base + cc * 8) = val;
                 }
+            }
+            if (F32 && nout.ss) {  // sums of squares of 64-column slices of the row: 16 lanes each
+                static_assert(!F32 || kChunksPerRow % 16 == 0, "a 64-column slice = 16 lanes of one row");
+                sq = row_sum16(sq);
+                if ((cc & 15) == 0 && row < M)
+                    nout.ss[(int64_t)row * (N / 64) + (col_base + cc * 4) / 64] = sq;
             }
         }
     }
@@ -228,7 +294,8 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
 
 template <int EPI, int WM, int WN, int kStages>
 hipError_t launch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, int K, void *C,
-                  int64_t ldc, const float *resid, int64_t ldr, hipStream_t s)
+                  int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &nin, const RowNormOut &nout,
+                  hipStream_t s)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr size_t lds_bytes = (size_t)kStages * (BM + BN) * BK * 2;
@@ -238,13 +305,14 @@ hipError_t launch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, i
     if (attr != hipSuccess) return attr;
     const dim3 grid(N / BN, (M + BM - 1) / BM), block(256);
     hipLaunchKernelGGL((gemm_bf16_kernel<EPI, WM, WN, kStages>), grid, block, lds_bytes, s, a, lda, w, M, N, K,
-                       C, ldc, resid, ldr);
+                       C, ldc, resid, ldr, nin, nout);
     return hipGetLastError();
 }
 
 template <int EPI>
 hipError_t dispatch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, int K, void *C,
-                    int64_t ldc, const float *resid, int64_t ldr, hipStream_t s)
+                    int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &nin,
+                    const RowNormOut &nout, hipStream_t s)
 {
     // CLIMBER_GEMM_TILE=44|42|22 overrides the choice, for tuning
     static const int forced = [] { const char *e = getenv("CLIMBER_GEMM_TILE"); return e ? atoi(e) : 0; }();
@@ -253,9 +321,9 @@ hipError_t dispatch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N,
         const int64_t mid = (int64_t)(N / 128) * ((M + 255) / 256);
         tile = mid >= 512 ? 42 : 22;
     }
-    if (tile == 44 && N % 256 == 0) return launch<EPI, 4, 4, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
-    if (tile == 42) return launch<EPI, 4, 2, 3>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
-    return launch<EPI, 2, 2, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
+    if (tile == 44 && N % 256 == 0) return launch<EPI, 4, 4, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
+    if (tile == 42) return launch<EPI, 4, 2, 3>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
+    return launch<EPI, 2, 2, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
 }
 
 }  // namespace
@@ -281,15 +349,16 @@ hipError_t pack_weights(const PackJobs &jobs, hipStream_t s)
 }
 
 hipError_t gemm_bf16(int epi, const void *A, int64_t lda, const void *w_packed, int M, int N, int K,
-                     void *C, int64_t ldc, const float *resid, int64_t ldr, hipStream_t s)
+                     void *C, int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &nin,
+                     const RowNormOut &nout, hipStream_t s)
 {
     if (M <= 0) return hipSuccess;
     if (N % 128 != 0 || K % 64 != 0) return hipErrorInvalidValue;
     const __bf16 *a = (const __bf16 *)A, *w = (const __bf16 *)w_packed;
     switch (epi) {
-    case EPI_STORE_BF16: return dispatch<EPI_STORE_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
-    case EPI_GELU_BF16: return dispatch<EPI_GELU_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
-    case EPI_RESID_F32: return dispatch<EPI_RESID_F32>(a, lda, w, M, N, K, C, ldc, resid, ldr, s);
+    case EPI_STORE_BF16: return dispatch<EPI_STORE_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
+    case EPI_GELU_BF16: return dispatch<EPI_GELU_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
+    case EPI_RESID_F32: return dispatch<EPI_RESID_F32>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
     default: return hipErrorInvalidValue;
     }
 }

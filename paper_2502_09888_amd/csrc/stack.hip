@@ -2,7 +2,11 @@
 // layers -- history encode (fills every layer of the KV cache) and candidate scoring against it.
 // Layer composition (the paper leaves f_QKV / f_FFN of Eq. (3) open; this build fixes it):
 //   qkv = RMSNorm(x; g1) Wqkv;  o = attention;  h = x + o Wo;  y = h + GELU(RMSNorm(h; g2) W1) W2
-// The residual stream is fp32, GEMM operands are bf16, accumulation is fp32.
+// The residual stream is fp32, GEMM operands are bf16, accumulation is fp32.  RMSNorm never runs
+// as a kernel of its own: RMSNorm(x; g) W = r * (x (g (.) W)) with r = 1/sqrt(mean(x^2) + eps) per
+// row, so the gains are folded into the weight rows when the weights are repacked, the projection
+// that produces x also emits its bf16 copy and the row sums of squares, and the projection that
+// consumes it scales its output rows by r.
 #include "stack.h"
 
 #include <algorithm>
@@ -19,7 +23,8 @@ size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 struct Workspace {
     float *x32;     // [rows][d]   residual stream of encode / score
     float *h32;     // [rows][d]   post-attention residual
-    uint8_t *xn;    // [rows][d]   bf16 normalised rows
+    uint8_t *xb;    // [rows][d]   bf16 copy of the rows the next projection normalises
+    float *ss;      // [rows][d/64] partial sums of squares of those rows
     uint8_t *qkv;   // [rows][3d]  bf16 fused projection output
     uint8_t *o;     // [rows][d]   bf16 attention output
     uint8_t *u;     // [rows][F]   bf16 FFN hidden
@@ -39,7 +44,8 @@ Workspace carve(const climber_config *c, int64_t rows, void *base)
     Workspace w;
     w.x32 = (float *)take(n * d * 4);
     w.h32 = (float *)take(n * d * 4);
-    w.xn = take(n * d * 2);
+    w.xb = take(n * d * 2);
+    w.ss = (float *)take(n * (d / 64) * 4);
     w.qkv = take(n * 3 * d * 2);
     w.o = take(n * d * 2);
     w.u = take(n * F * 2);
@@ -85,10 +91,12 @@ int pack_layers(const climber_config *cfg, const climber_layer_weights *layers, 
     for (int l = 0; l < n; ++l) {
         const PackedLayer pl = packed_layer(cfg, ws, l);
         const void *src[4] = {layers[l].wqkv, layers[l].wo, layers[l].w1, layers[l].w2};
+        const void *gain[4] = {layers[l].g1, nullptr, layers[l].g2, nullptr};
         const uint8_t *dst[4] = {pl.wqkv, pl.wo, pl.w1, pl.w2};
         const int K[4] = {d, d, d, F}, N[4] = {3 * d, d, F, d};
         for (int i = 0; i < 4; ++i) {
             jobs.w[jobs.n] = src[i];
+            jobs.gain[jobs.n] = gain[i];
             jobs.packed[jobs.n] = const_cast<uint8_t *>(dst[i]);
             jobs.K[jobs.n] = K[i];
             jobs.N[jobs.n] = N[i];
@@ -102,20 +110,19 @@ int pack_layers(const climber_config *cfg, const climber_layer_weights *layers, 
     return CLIMBER_OK;
 }
 
-// one layer on `rows` rows.  The input rows are either the fp32 stream x_in or, for the first layer
-// of a stack call, the bf16 embeddings x_in_bf16, which are widened into x_in on the way.
-int run_layer(const climber_config *cfg, const climber_layer_weights *w, const PackedLayer &pw,
-              const float *tau_layer, int32_t layer, int32_t mode, climber_kv_cache *cache,
-              const void *x_in_bf16, float *x_in, float *x_out, const int32_t *scen, const int32_t *beh,
-              const int32_t *cand_off, int32_t m_total, int32_t m_max, int64_t rows, const Workspace &ws,
-              hipStream_t s)
+// one layer on `rows` rows.  x_in: fp32 rows (the residual stream); xb_in / ws.ss: their bf16 copy and
+// row sums of squares (from the previous layer's last projection or from a row_prep kernel).
+// norm_out: also emit the bf16 copy and sums of squares of x_out (the next layer needs them).
+int run_layer(const climber_config *cfg, const PackedLayer &pw, const float *tau_layer, int32_t layer,
+              int32_t mode, climber_kv_cache *cache, const float *x_in, const void *xb_in, float *x_out,
+              bool norm_out, const int32_t *scen, const int32_t *beh, const int32_t *cand_off,
+              int32_t m_total, int32_t m_max, int64_t rows, const Workspace &ws, hipStream_t s)
 {
     const int d = cfg->d_model, F = cfg->d_ffn, M = (int)rows;
-    if (x_in_bf16)
-        TRY(rt(rmsnorm_from_bf16(x_in_bf16, w->g1, ws.xn, x_in, rows, d, cfg->rms_eps, s)));
-    else
-        TRY(rt(rmsnorm_to_bf16(x_in, w->g1, ws.xn, rows, d, cfg->rms_eps, s)));
-    TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xn, d, pw.wqkv, M, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, s)));
+    const RowNormIn nin{ws.ss, d / 64, 1.f / (float)d, cfg->rms_eps}, no_in{nullptr, 0, 0.f, 0.f};
+    const RowNormOut nout{ws.ss, ws.xb, d}, no_out{nullptr, nullptr, 0};
+    TRY(rt(gemm_bf16(EPI_STORE_BF16, xb_in, d, pw.wqkv, M, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, nin,
+                     no_out, s)));
     const uint8_t *q = ws.qkv, *k = ws.qkv + (size_t)d * 2, *v = ws.qkv + (size_t)2 * d * 2;
     if (mode == CLIMBER_MODE_HISTORY) {
         TRY(attn_history_strided(cfg, tau_layer, q, k, v, 3 * d, scen, beh, cache, layer,
@@ -125,10 +132,10 @@ int run_layer(const climber_config *cfg, const climber_layer_weights *w, const P
         TRY(attn_sumi_strided(cfg, tau_layer, cache, layer, q, k, v, 3 * d, cand_off, m_total, m_max,
                               scen, beh, ws.o, d, s));
     }
-    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o, d, pw.wo, M, d, d, ws.h32, d, x_in, d, s)));
-    TRY(rt(rmsnorm_to_bf16(ws.h32, w->g2, ws.xn, rows, d, cfg->rms_eps, s)));
-    TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xn, d, pw.w1, M, F, d, ws.u, F, nullptr, 0, s)));
-    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.u, F, pw.w2, M, d, F, x_out, d, ws.h32, d, s)));
+    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o, d, pw.wo, M, d, d, ws.h32, d, x_in, d, no_in, nout, s)));
+    TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xb, d, pw.w1, M, F, d, ws.u, F, nullptr, 0, nin, no_out, s)));
+    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.u, F, pw.w2, M, d, F, x_out, d, ws.h32, d, no_in,
+                     norm_out ? nout : no_out, s)));
     return CLIMBER_OK;
 }
 
@@ -187,8 +194,9 @@ int climber_layer_forward(const climber_config *cfg, const climber_layer_weights
     if (rows == 0) return CLIMBER_OK;
     hipStream_t s = (hipStream_t)stream;
     TRY(pack_layers(cfg, w, 1, ws, s));
-    return run_layer(cfg, w, packed_layer(cfg, ws, 0), tau_layer, layer, mode, cache, nullptr,
-                     const_cast<float *>(x_in), x_out, scen, beh, cand_off, m_total, m_max, rows, ws, s);
+    TRY(rt(row_prep_f32(x_in, ws.xb, ws.ss, cfg->d_model / 64, rows, cfg->d_model, s)));
+    return run_layer(cfg, packed_layer(cfg, ws, 0), tau_layer, layer, mode, cache, x_in, ws.xb, x_out,
+                     false, scen, beh, cand_off, m_total, m_max, rows, ws, s);
 }
 
 int climber_history_encode(const climber_config *cfg, const climber_weights *weights,
@@ -211,12 +219,13 @@ int climber_history_encode(const climber_config *cfg, const climber_weights *wei
     if (rows == 0) return CLIMBER_OK;
     hipStream_t s = (hipStream_t)stream;
     TRY(pack_layers(cfg, weights->layers, cfg->n_layers, ws, s));
+    TRY(rt(row_prep_bf16(x_hist, ws.x32, ws.ss, cfg->d_model / 64, rows, cfg->d_model, s)));
     const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
     for (int l = 0; l < cfg->n_layers; ++l) {
         const bool last = l + 1 == cfg->n_layers;  // nothing reads the last layer's history output
-        TRY(run_layer(cfg, &weights->layers[l], packed_layer(cfg, ws, l), tau + l * tl, l,
-                      CLIMBER_MODE_HISTORY, cache, l == 0 ? x_hist : nullptr, ws.x32,
-                      last ? nullptr : ws.x32, scen, beh, nullptr, 0, 0, rows, ws, s));
+        TRY(run_layer(cfg, packed_layer(cfg, ws, l), tau + l * tl, l, CLIMBER_MODE_HISTORY, cache,
+                      ws.x32, l == 0 ? x_hist : (const void *)ws.xb, last ? nullptr : ws.x32, !last, scen,
+                      beh, nullptr, 0, 0, rows, ws, s));
     }
     return CLIMBER_OK;
 }
@@ -242,14 +251,15 @@ int climber_sumi_score(const climber_config *cfg, const climber_weights *weights
     if (m_total == 0) return CLIMBER_OK;
     hipStream_t s = (hipStream_t)stream;
     TRY(pack_layers(cfg, weights->layers, cfg->n_layers, ws, s));
+    TRY(rt(row_prep_bf16(x_cand, ws.x32, ws.ss, cfg->d_model / 64, m_total, cfg->d_model, s)));
     const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
     for (int l = 0; l < cfg->n_layers; ++l) {
         const bool last = l + 1 == cfg->n_layers;
         // the cache is only read in candidate mode
-        TRY(run_layer(cfg, &weights->layers[l], packed_layer(cfg, ws, l), tau + l * tl, l,
-                      CLIMBER_MODE_CANDIDATE, const_cast<climber_kv_cache *>(cache),
-                      l == 0 ? x_cand : nullptr, ws.x32, last ? y_cand : ws.x32, cand_scen, cand_beh,
-                      cand_off, m_total, m_max, m_total, ws, s));
+        TRY(run_layer(cfg, packed_layer(cfg, ws, l), tau + l * tl, l, CLIMBER_MODE_CANDIDATE,
+                      const_cast<climber_kv_cache *>(cache), ws.x32, l == 0 ? x_cand : (const void *)ws.xb,
+                      last ? y_cand : ws.x32, !last, cand_scen, cand_beh, cand_off, m_total, m_max,
+                      m_total, ws, s));
     }
     return CLIMBER_OK;
 }

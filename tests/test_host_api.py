@@ -100,7 +100,7 @@ def test_compute_calls_reject_missing_cache_and_pointers():
 def test_workspace_bytes():
     c4 = P.Config(n_layers=4, n_heads=8, d_head=64, d_ffn=2048, n_scen=8, n_beh=4, sub_len=256)
     n = 32768
-    need = n * 512 * (4 + 4 + 2 + 6 + 2) + n * 2048 * 2 + 4 * 2 * (4 * 512 * 512 + 2 * 512 * 2048)
+    need = n * 512 * (4 + 4 + 2 + 6 + 2) + n * 8 * 4 + n * 2048 * 2 + 4 * 2 * (4 * 512 * 512 + 2 * 512 * 2048)
     got = P.climber_workspace_bytes(c4, n)
     assert need <= got <= need + 8 * 256
     assert P.climber_workspace_bytes(cfg(dtype=P.F32, d_head=32, sub_len=0), 10) == 0
