@@ -37,11 +37,20 @@ struct PackJobs {
 };
 hipError_t pack_weights(const PackJobs &jobs, hipStream_t s);
 
-// C = A W (+ epilogue).  A: bf16 [M][lda]; w_packed from pack_weight; N % 128 == 0, K % 64 == 0.
-// EPI_STORE_BF16 / EPI_GELU_BF16: C is bf16 [M][ldc].  EPI_RESID_F32: C is fp32, C = acc + resid.
+// Tiled activation layout (bf16, X columns): the rows are cut into groups of 16 and the columns into
+// k-tiles of 32; piece (g, t) = 1 KiB at ((g * X/32) + t) * 1024, holding for row r of the group and
+// 16-byte slot s (at r*64 + s*16) the 8 columns 32t + 8(s ^ (r >> 2)) ..: exactly the bytes one
+// global->LDS copy of the consuming projection lands, so that the copy reads 1 KiB contiguous and
+// the k-tiles of a row group follow each other in memory.  Buffers hold a multiple of 16 rows.
+// Used for the FFN hidden (X = d_ffn: with row-major rows a copy would touch 16 rows 4 KiB apart).
+enum { kTiledA = 1, kTiledC = 2 };
+
+// C = A W (+ epilogue).  A: bf16 [M][lda], or tiled (kTiledA; lda unused); w_packed from pack_weight;
+// N % 128 == 0, K % 64 == 0.  EPI_STORE_BF16 / EPI_GELU_BF16: C is bf16 [M][ldc] (EPI_GELU_BF16 with
+// kTiledC: tiled, ldc unused).  EPI_RESID_F32: C is fp32, C = acc + resid.
 hipError_t gemm_bf16(int epi, const void *A, int64_t lda, const void *w_packed, int M, int N, int K,
                      void *C, int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &in_norm,
-                     const RowNormOut &out_norm, hipStream_t s);
+                     const RowNormOut &out_norm, int tiled, hipStream_t s);
 
 // What the first projection of a stack call needs of its input rows: the sum of squares of every
 // row into ss[row][0] (ss[row][1 .. n_part-1] = 0) and

@@ -5,23 +5,24 @@
 // W is first repacked (pack_weight) into B-operand fragments of v_mfma_f32_32x32x16_bf16:
 //   chunk (nb, ks, lane), 16 B: W[16ks + 8(lane/32) + 0..7][32nb + lane%32]
 // so that a k-tile of a 32-column block is contiguous and is copied HBM -> LDS linearly.
-// A stays row-major; its tile is copied row by row (64 B per row and k-tile) with the 16-byte
-// chunks of a row XOR-swizzled through the choice of the global address each lane loads, so that
-// the fragment reads (32 rows, same k chunk) are conflict free.
-// Both copies are direct global_load_lds (no register staging) into a ring of 4 k-tiles of 32,
-// two to three tiles in flight, one bare s_barrier per k-tile.
+// A is row-major (its tile is copied row by row, 64 B per row and k-tile, with the 16-byte chunks
+// of a row XOR-swizzled by (row / 4) % 4 through the choice of the global address each lane loads:
+// 16 consecutive rows of one k chunk then cover all 64 banks) or in the tiled layout of gemm.h,
+// where one copy is 1 KiB contiguous.
+// Both copies are direct global_load_lds (no register staging) into a ring of 3 or 4 k-tiles of 32,
+// one or two tiles in flight, one bare s_barrier per k-tile; the copies of a k-tile are dealt out
+// between the MFMAs of the tile two ahead of it, not queued in front of them.
 // Workgroup = 4 waves as 2 x 2; a wave owns WM x WN blocks of 32 x 32:
-//   4 x 4 (macro tile 256 x 256): half an LDS fragment read per MFMA -- the shape that keeps the
-//         matrix pipe, not LDS bandwidth, the limit; accumulators (256 registers) live in AGPRs;
-//   4 x 2 (macro tile 256 x 128): 128 accumulator registers, two workgroups per CU, so that one's
-//         prologue / epilogue overlaps the other's k-loop (the projections here have K = 512 or
-//         2048: short k-loops, and they sit near the HBM/MFMA ridge);
+//   4 x 2 (macro tile 256 x 128): 128 accumulator registers, two workgroups per CU (the projections
+//         here have K = 512 or 2048: short k-loops, and they sit near the HBM/MFMA ridge);
 //   2 x 2 (macro tile 128 x 128): for problems too small to fill the chip with larger tiles.
+// Workgroups that share A rows are launched onto the same XCD (see the kernel).
 #include "gemm.h"
 
 #include <algorithm>
 #include <cstdlib>
 #include <type_traits>
+#include <utility>
 
 namespace climber {
 namespace {
@@ -96,6 +97,18 @@ __device__ __forceinline__ float row_sum16(float x)
     return x;
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), unrolled at compile time
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vm()
 {
@@ -111,9 +124,9 @@ __device__ __forceinline__ void wait_vm()
 
 // WM, WN: 32 x 32 blocks per wave along M and N.  Macro tile (2*WM*32) x (2*WN*32) x 32.
 template <int EPI, int WM, int WN, int kStages>
-__global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
+__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
     const __bf16 *A, int64_t lda, const __bf16 *Wp, int M, int N, int K, void *C, int64_t ldc,
-    const float *resid, int64_t ldr, const RowNormIn nin, const RowNormOut nout)
+    const float *resid, int64_t ldr, const RowNormIn nin, const RowNormOut nout, const int tiled)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr int kABytes = BM * BK * 2, kBBytes = BN * BK * 2, kStageBytes = kABytes + kBBytes;
@@ -124,16 +137,28 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    // Tile of this workgroup.  Workgroups are dealt to the 8 XCDs round-robin in launch order and
+    // every XCD has an L2 of its own; the n_col workgroups that share a block of A rows are therefore
+    // given launch indices that are equal modulo 8 (one XCD, adjacent in time), so that the rows
+    // come from HBM once instead of once per XCD.
+    const int n_col = N / BN, n_tiles = n_col * ((M + BM - 1) / BM);
+    int tile = blockIdx.x;
+    if (n_tiles % 8 == 0) tile = (tile & 7) * (n_tiles >> 3) + (tile >> 3);
+    const int m0 = (tile / n_col) * BM, n0 = (tile % n_col) * BN;
     const int n_kt = K / BK;
 
     // copy plan.  A: copy j of this wave covers rows 16*(wave*NA + j) .. +15, lane -> (row, slot),
-    // global chunk = slot ^ ((row >> 1) & 3).  W: copy j covers fragment (nbl, ksl) of the tile.
+    // global chunk = slot ^ ((row >> 2) & 3).  W: copy j covers fragment (nbl, ksl) of the tile.
     const __bf16 *a_src[NA];
+    const bool a_tiled = tiled & kTiledA;
+    const int a_step = a_tiled ? 512 : BK;   // elements from one k-tile of a copy to the next
 #pragma unroll
     for (int j = 0; j < NA; ++j) {
         const int r = 16 * (wave * NA + j) + (lane >> 2), slot = lane & 3;
-        a_src[j] = A + (int64_t)min(m0 + r, M - 1) * lda + ((slot ^ ((r >> 1) & 3)) * 8);
+        if (a_tiled)   // the 1 KiB piece is stored as it lands in LDS, swizzle included
+            a_src[j] = A + (int64_t)min((m0 >> 4) + wave * NA + j, (M - 1) >> 4) * (K / BK) * 512 + lane * 8;
+        else
+            a_src[j] = A + (int64_t)min(m0 + r, M - 1) * lda + ((slot ^ ((r >> 2) & 3)) * 8);
     }
     const uint8_t *w_src[NB];
 #pragma unroll
@@ -142,16 +167,18 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
         w_src[j] = (const uint8_t *)Wp +
                    (((int64_t)(n0 / 32 + nbl) * (K / 16) + ksl) * 64 + lane) * 16;
     }
-    auto issue = [&](int kt) __attribute__((always_inline)) {
+    // copy c (0 .. NPRE-1) of k-tile kt: NA pieces of the A tile, then NB pieces of the W tile
+    auto issue_one = [&](int kt, auto c_tag) __attribute__((always_inline)) {
+        constexpr int c = decltype(c_tag)::value;
         lds_u8 *base = (lds_u8 *)lds + (kt % kStages) * kStageBytes;
-#pragma unroll
-        for (int j = 0; j < NA; ++j)
-            __builtin_amdgcn_global_load_lds((glb_u8 *)(a_src[j] + kt * BK),
-                                             base + (wave * NA + j) * 1024, 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
-            __builtin_amdgcn_global_load_lds((glb_u8 *)(w_src[j] + (int64_t)kt * 2048),
-                                             base + kABytes + (wave * NB + j) * 1024, 16, 0, 0);
+        if constexpr (c < NA)
+            __builtin_amdgcn_global_load_lds((glb_u8 *)(a_src[c] + kt * a_step), base + (wave * NA + c) * 1024, 16, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds((glb_u8 *)(w_src[c - NA] + (int64_t)kt * 2048),
+                                             base + kABytes + (wave * NB + (c - NA)) * 1024, 16, 0, 0);
+    };
+    auto issue = [&](int kt) __attribute__((always_inline)) {
+        static_for<NPRE>([&](auto c) __attribute__((always_inline)) { issue_one(kt, c); });
     };
 
     f32x16 acc[WM][WN];
@@ -179,33 +206,45 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
     }
 
     for (int kt = 0; kt < kStages - 1 && kt < n_kt; ++kt) issue(kt);
-    for (int kt = 0; kt < n_kt; ++kt) {
-        // tiles kt+1 .. kt+kStages-2 may stay in flight
-        const int ahead = min(kt + kStages - 1, n_kt) - (kt + 1);
+    // One k-tile: wait for it, read both halves' fragments, then the MFMAs with the copies of tile
+    // kt + kStages - 1 (if PREFETCH) dealt out between them, one copy after every kStep-th MFMA, so
+    // that a wave never queues its copies back to back in front of its own MFMAs.
+    constexpr int kMfma = 2 * WM * WN, kStep = kMfma / NPRE >= 1 ? kMfma / NPRE : 1;
+    auto k_tile = [&](int kt, auto prefetch_tag) __attribute__((always_inline)) {
+        constexpr bool PREFETCH = decltype(prefetch_tag)::value;
+        const int ahead = min(kt + kStages - 1, n_kt) - (kt + 1);  // tiles that may stay in flight
         if (kStages > 3 && ahead >= 2) wait_vm<(kStages > 3 ? 2 : 1) * NPRE>();
         else if (ahead >= 1) wait_vm<NPRE>();
         else wait_vm<0>();
         __builtin_amdgcn_s_barrier();
-        if (kt + kStages - 1 < n_kt) issue(kt + kStages - 1);
         const uint8_t *sa = lds + (kt % kStages) * kStageBytes;
         const uint8_t *sw = sa + kABytes;
+        bf16x8 af[2][WM], bfr[2][WN];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            bf16x8 af[WM], bfr[WN];
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
                 const int row = 32 * (WM * wm + i) + l32;
-                af[i] = *(const bf16x8 *)(sa + row * 64 + (((2 * ks + hf) ^ ((row >> 1) & 3)) * 16));
+                af[ks][i] = *(const bf16x8 *)(sa + row * 64 + (((2 * ks + hf) ^ ((row >> 2) & 3)) * 16));
             }
 #pragma unroll
             for (int j = 0; j < WN; ++j)
-                bfr[j] = *(const bf16x8 *)(sw + (((WN * wn + j) * 2 + ks) * 64 + lane) * 16);
-#pragma unroll
-            for (int i = 0; i < WM; ++i)
-#pragma unroll
-                for (int j = 0; j < WN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+                bfr[ks][j] = *(const bf16x8 *)(sw + (((WN * wn + j) * 2 + ks) * 64 + lane) * 16);
         }
+        static_for<kMfma>([&](auto m_tag) __attribute__((always_inline)) {
+                constexpr int Ms = decltype(m_tag)::value;
+                constexpr int ks = Ms / (WM * WN), i = (Ms % (WM * WN)) / WN, j = Ms % WN;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
+                if constexpr (PREFETCH && Ms % kStep == 0 && Ms / kStep < NPRE) {
+                    issue_one(kt + kStages - 1, std::integral_constant<int, Ms / kStep>{});
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        });
+    };
+    {
+        int kt = 0;
+        for (; kt + kStages - 1 < n_kt; ++kt) k_tile(kt, std::true_type{});
+        for (; kt < n_kt; ++kt) k_tile(kt, std::false_type{});
     }
 
     // Epilogue.  The operands were fed as (W fragment, A fragment), so a block accumulator is the
@@ -237,6 +276,23 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
     constexpr int kPitch = CW * kElem + 16;           // bytes per staged row
     constexpr int kChunksPerRow = CW * kElem / 16;
     uint8_t *tr = lds + wave * (32 * kPitch);
+    constexpr int kIters = 32 * kChunksPerRow / 64;   // 16-byte pieces per lane and block row
+    const int col_base = n0 + CW * wn;
+    // Residual rows of block row i, all requested before anything waits for them (a load placed
+    // after a store would make the wait for it drain the stores as well: one memory round trip per
+    // 16 bytes).  Block row i + 1 is requested before block row i is stored.
+    float4 rsd[2][F32 ? kIters : 1];
+    auto load_resid = [&](int i, float4 *buf) __attribute__((always_inline)) {
+        if constexpr (F32) {
+#pragma unroll
+            for (int it = 0; it < kIters; ++it) {
+                const int id = it * 64 + lane, r = id / kChunksPerRow, cc = id % kChunksPerRow;
+                const int row = min(m0 + 32 * (WM * wm + i) + r, M - 1);
+                buf[it] = *(const float4 *)(resid + (int64_t)row * ldr + col_base + cc * 4);
+            }
+        }
+    };
+    load_resid(0, rsd[0]);
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
 #pragma unroll
@@ -257,36 +313,43 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
                     *(uint2 *)(tr + l32 * kPitch + col * 2) = *(const uint2 *)v;
                 }
             }
+        if (i + 1 < WM) load_resid(i + 1, rsd[(i + 1) & 1]);
         const int row_base = m0 + 32 * (WM * wm + i);
-        const int col_base = n0 + CW * wn;
 #pragma unroll
-        for (int it = 0; it < 32 * kChunksPerRow / 64; ++it) {
+        for (int it = 0; it < kIters; ++it) {
             const int id = it * 64 + lane, r = id / kChunksPerRow, cc = id % kChunksPerRow;
             const int row = row_base + r;
             uint4 val = *(const uint4 *)(tr + r * kPitch + cc * 16);
-            float sq = 0.f;
-            if (row < M) {
-                if (F32) {
-                    const int col = col_base + cc * 4;
-                    const float4 rsd = *(const float4 *)(resid + (int64_t)row * ldr + col);
-                    float4 o = *(const float4 *)&val;
-                    o.x += rsd.x; o.y += rsd.y; o.z += rsd.z; o.w += rsd.w;
+            if (F32) {
+                const int col = col_base + cc * 4;
+                const float4 rd = rsd[i & 1][it];
+                float4 o = *(const float4 *)&val;
+                o.x += rd.x; o.y += rd.y; o.z += rd.z; o.w += rd.w;
+                if (row < M) {
                     *(float4 *)((float *)C + (int64_t)row * ldc + col) = o;
                     if (nout.ss) {
                         bf16x4 ob;
                         ob[0] = (__bf16)o.x; ob[1] = (__bf16)o.y; ob[2] = (__bf16)o.z; ob[3] = (__bf16)o.w;
                         *(bf16x4 *)((__bf16 *)nout.xb + (int64_t)row * nout.ldb + col) = ob;
                     }
-                    sq = o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
-                } else {
-                    *(uint4 *)((__bf16 *)C + (int64_t)row * ldc + col_base + cc * 8) = val;
                 }
-            }
-            if (F32 && nout.ss) {  // sums of squares of 64-column slices of the row: 16 lanes each
-                static_assert(!F32 || kChunksPerRow % 16 == 0, "a 64-column slice = 16 lanes of one row");
-                sq = row_sum16(sq);
-                if ((cc & 15) == 0 && row < M)
-                    nout.ss[(int64_t)row * (N / 64) + (col_base + cc * 4) / 64] = sq;
+                if (nout.ss) {  // sums of squares of 64-column slices of the row: 16 lanes each
+                    static_assert(!F32 || kChunksPerRow % 16 == 0, "a 64-column slice = 16 lanes of one row");
+                    const float sq = row_sum16(o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w);
+                    if ((cc & 15) == 0 && row < M)
+                        nout.ss[(int64_t)row * (N / 64) + (col_base + cc * 4) / 64] = sq;
+                }
+            } else if (EPI == EPI_GELU_BF16 && (tiled & kTiledC)) {
+                // piece `it` = (16-row group it / 2, k-tile it % 2) of the block; a lane takes the chunk
+                // that the consuming projection's copy puts at its place in LDS
+                static_assert(EPI != EPI_GELU_BF16 || (CW == 64 && kIters == 4), "block = 2 x 2 pieces");
+                const int rr = 16 * (it >> 1) + (lane >> 2), c = (lane & 3) ^ ((lane >> 4) & 3);
+                val = *(const uint4 *)(tr + rr * kPitch + ((it & 1) * 4 + c) * 16);
+                if (row_base + rr < M)
+                    *(uint4 *)((uint8_t *)C + ((int64_t)((row_base >> 4) + (it >> 1)) * (N / 32) +
+                                               (col_base >> 5) + (it & 1)) * 1024 + lane * 16) = val;
+            } else if (row < M) {
+                *(uint4 *)((__bf16 *)C + (int64_t)row * ldc + col_base + cc * 8) = val;
             }
         }
     }
@@ -295,7 +358,7 @@ __global__ __launch_bounds__(256, (WM * WN > 8) ? 1 : 2) void gemm_bf16_kernel(
 template <int EPI, int WM, int WN, int kStages>
 hipError_t launch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, int K, void *C,
                   int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &nin, const RowNormOut &nout,
-                  hipStream_t s)
+                  int tiled, hipStream_t s)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr size_t lds_bytes = (size_t)kStages * (BM + BN) * BK * 2;
@@ -303,27 +366,26 @@ hipError_t launch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, i
         (const void *)gemm_bf16_kernel<EPI, WM, WN, kStages>, hipFuncAttributeMaxDynamicSharedMemorySize,
         (int)lds_bytes);
     if (attr != hipSuccess) return attr;
-    const dim3 grid(N / BN, (M + BM - 1) / BM), block(256);
+    const dim3 grid((N / BN) * ((M + BM - 1) / BM)), block(256);
     hipLaunchKernelGGL((gemm_bf16_kernel<EPI, WM, WN, kStages>), grid, block, lds_bytes, s, a, lda, w, M, N, K,
-                       C, ldc, resid, ldr, nin, nout);
+                       C, ldc, resid, ldr, nin, nout, tiled);
     return hipGetLastError();
 }
 
 template <int EPI>
 hipError_t dispatch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, int K, void *C,
                     int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &nin,
-                    const RowNormOut &nout, hipStream_t s)
+                    const RowNormOut &nout, int tiled, hipStream_t s)
 {
-    // CLIMBER_GEMM_TILE=44|42|22 overrides the choice, for tuning
+    // CLIMBER_GEMM_TILE=42|22 overrides the choice, for tuning
     static const int forced = [] { const char *e = getenv("CLIMBER_GEMM_TILE"); return e ? atoi(e) : 0; }();
     int tile = forced;
     if (tile == 0) {
         const int64_t mid = (int64_t)(N / 128) * ((M + 255) / 256);
         tile = mid >= 512 ? 42 : 22;
     }
-    if (tile == 44 && N % 256 == 0) return launch<EPI, 4, 4, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
-    if (tile == 42) return launch<EPI, 4, 2, 3>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
-    return launch<EPI, 2, 2, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
+    if (tile == 42) return launch<EPI, 4, 2, 3>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, s);
+    return launch<EPI, 2, 2, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, s);
 }
 
 }  // namespace
@@ -350,15 +412,16 @@ hipError_t pack_weights(const PackJobs &jobs, hipStream_t s)
 
 hipError_t gemm_bf16(int epi, const void *A, int64_t lda, const void *w_packed, int M, int N, int K,
                      void *C, int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &nin,
-                     const RowNormOut &nout, hipStream_t s)
+                     const RowNormOut &nout, int tiled, hipStream_t s)
 {
     if (M <= 0) return hipSuccess;
     if (N % 128 != 0 || K % 64 != 0) return hipErrorInvalidValue;
+    if ((tiled & ~(kTiledA | kTiledC)) || ((tiled & kTiledC) && epi != EPI_GELU_BF16)) return hipErrorInvalidValue;
     const __bf16 *a = (const __bf16 *)A, *w = (const __bf16 *)w_packed;
     switch (epi) {
-    case EPI_STORE_BF16: return dispatch<EPI_STORE_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
-    case EPI_GELU_BF16: return dispatch<EPI_GELU_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
-    case EPI_RESID_F32: return dispatch<EPI_RESID_F32>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, s);
+    case EPI_STORE_BF16: return dispatch<EPI_STORE_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, s);
+    case EPI_GELU_BF16: return dispatch<EPI_GELU_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, s);
+    case EPI_RESID_F32: return dispatch<EPI_RESID_F32>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -27,7 +27,7 @@ struct Workspace {
     float *ss;      // [rows][d/64] partial sums of squares of those rows
     uint8_t *qkv;   // [rows][3d]  bf16 fused projection output
     uint8_t *o;     // [rows][d]   bf16 attention output
-    uint8_t *u;     // [rows][F]   bf16 FFN hidden
+    uint8_t *u;     // bf16 FFN hidden, tiled layout (gemm.h), rows rounded up to 16
     uint8_t *wpack; // packed weights of every layer: [layer]{wqkv, wo, w1, w2}
     size_t wlayer;  // bytes of one layer's packed weights
     size_t total;
@@ -48,7 +48,7 @@ Workspace carve(const climber_config *c, int64_t rows, void *base)
     w.ss = (float *)take(n * (d / 64) * 4);
     w.qkv = take(n * 3 * d * 2);
     w.o = take(n * d * 2);
-    w.u = take(n * F * 2);
+    w.u = take((n + 15) / 16 * 16 * F * 2);
     w.wlayer = up256((4 * d * d + 2 * d * F) * 2);
     w.wpack = take(w.wlayer * (size_t)std::max(c->n_layers, 1));
     w.total = off;
@@ -122,7 +122,7 @@ int run_layer(const climber_config *cfg, const PackedLayer &pw, const float *tau
     const RowNormIn nin{ws.ss, d / 64, 1.f / (float)d, cfg->rms_eps}, no_in{nullptr, 0, 0.f, 0.f};
     const RowNormOut nout{ws.ss, ws.xb, d}, no_out{nullptr, nullptr, 0};
     TRY(rt(gemm_bf16(EPI_STORE_BF16, xb_in, d, pw.wqkv, M, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, nin,
-                     no_out, s)));
+                     no_out, 0, s)));
     const uint8_t *q = ws.qkv, *k = ws.qkv + (size_t)d * 2, *v = ws.qkv + (size_t)2 * d * 2;
     if (mode == CLIMBER_MODE_HISTORY) {
         TRY(attn_history_strided(cfg, tau_layer, q, k, v, 3 * d, scen, beh, cache, layer,
@@ -132,10 +132,10 @@ int run_layer(const climber_config *cfg, const PackedLayer &pw, const float *tau
         TRY(attn_sumi_strided(cfg, tau_layer, cache, layer, q, k, v, 3 * d, cand_off, m_total, m_max,
                               scen, beh, ws.o, d, s));
     }
-    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o, d, pw.wo, M, d, d, ws.h32, d, x_in, d, no_in, nout, s)));
-    TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xb, d, pw.w1, M, F, d, ws.u, F, nullptr, 0, nin, no_out, s)));
+    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o, d, pw.wo, M, d, d, ws.h32, d, x_in, d, no_in, nout, 0, s)));
+    TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xb, d, pw.w1, M, F, d, ws.u, F, nullptr, 0, nin, no_out, kTiledC, s)));
     TRY(rt(gemm_bf16(EPI_RESID_F32, ws.u, F, pw.w2, M, d, F, x_out, d, ws.h32, d, no_in,
-                     norm_out ? nout : no_out, s)));
+                     norm_out ? nout : no_out, kTiledA, s)));
     return CLIMBER_OK;
 }
 
