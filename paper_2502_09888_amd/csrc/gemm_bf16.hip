@@ -69,19 +69,21 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const PackJobs jobs)
 }
 
 // exact-erf GELU, erf by the rational/exponential formula 7.1.26 of Abramowitz & Stegun
-// (|error| <= 1.5e-7, far below the bf16 rounding of the result)
+// (|error| <= 1.5e-7, far below the bf16 rounding of the result).  With a = |x|, z = a/sqrt(2),
+// t = 1/(1 + p z) and h = (1 - erf z)/2 = (poly(t)/2) t exp(-z^2):
+//   GELU(x) = x (1 + erf(x/sqrt 2))/2 = max(x, 0) - a h        (x >= 0: x - x h;  x < 0: x h)
+// which needs no sign select; the constants carry the factors 1/2, 1/sqrt(2) and log2(e)/2.
 __device__ __forceinline__ float gelu_erf(float x)
 {
-    const float z = fabsf(x) * 0.70710678118654752f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.f));
-    float poly = fmaf(1.061405429f, t, -1.453152027f);
-    poly = fmaf(poly, t, 1.421413741f);
-    poly = fmaf(poly, t, -0.284496736f);
-    poly = fmaf(poly, t, 0.254829592f);
-    const float e = __builtin_amdgcn_exp2f(-z * z * 1.4426950408889634f);
-    const float erf_abs = 1.f - poly * t * e;
-    const float erf_x = x < 0.f ? -erf_abs : erf_abs;
-    return 0.5f * x * (1.f + erf_x);
+    const float a = __builtin_fabsf(x);
+    const float t = __builtin_amdgcn_rcpf(fmaf(a, 0.3275911f * 0.70710678118654752f, 1.f));
+    float poly = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+    poly = fmaf(poly, t, 0.5f * 1.421413741f);
+    poly = fmaf(poly, t, 0.5f * -0.284496736f);
+    poly = fmaf(poly, t, 0.5f * 0.254829592f);
+    const float e = __builtin_amdgcn_exp2f((x * x) * -0.72134752044448170f);
+    const float h = (poly * t) * e;
+    return fmaf(-a, h, fmaxf(x, 0.f));
 }
 
 // sum over the 16 lanes of a DPP row, in every lane of the row (cross-lane adds on the VALU)
@@ -220,8 +222,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
         const uint8_t *sa = lds + (kt % kStages) * kStageBytes;
         const uint8_t *sw = sa + kABytes;
         bf16x8 af[2][WM], bfr[2][WN];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        auto read_frags = [&](auto ks_tag) __attribute__((always_inline)) {
+            constexpr int ks = decltype(ks_tag)::value;
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
                 const int row = 32 * (WM * wm + i) + l32;
@@ -230,15 +232,23 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
 #pragma unroll
             for (int j = 0; j < WN; ++j)
                 bfr[ks][j] = *(const bf16x8 *)(sw + (((WN * wn + j) * 2 + ks) * 64 + lane) * 16);
-        }
+        };
+        // the second half's fragments are requested behind the first MFMA, not ahead of it: the four
+        // waves leave the barrier together and queue their reads at the one LDS port
+        read_frags(std::integral_constant<int, 0>{});
+        __builtin_amdgcn_sched_barrier(0);
         static_for<kMfma>([&](auto m_tag) __attribute__((always_inline)) {
-                constexpr int Ms = decltype(m_tag)::value;
-                constexpr int ks = Ms / (WM * WN), i = (Ms % (WM * WN)) / WN, j = Ms % WN;
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
-                if constexpr (PREFETCH && Ms % kStep == 0 && Ms / kStep < NPRE) {
-                    issue_one(kt + kStages - 1, std::integral_constant<int, Ms / kStep>{});
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+            constexpr int Ms = decltype(m_tag)::value;
+            constexpr int ks = Ms / (WM * WN), i = (Ms % (WM * WN)) / WN, j = Ms % WN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
+            if constexpr (Ms == 0) {
+                read_frags(std::integral_constant<int, 1>{});
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (PREFETCH && Ms % kStep == kStep - 1 && Ms / kStep < NPRE) {
+                issue_one(kt + kStages - 1, std::integral_constant<int, Ms / kStep>{});
+                __builtin_amdgcn_sched_barrier(0);
+            }
         });
     };
     {
