@@ -32,6 +32,16 @@ def test_small_stack_all_users():
     run(spec, users=(0, 1))
 
 
+def test_small_stack_ragged_lengths_nan_padding():
+    # ragged histories (one shorter than a subsequence, one with a partial last subsequence and a
+    # partial last 32-key block), ragged candidate counts (one user without candidates), NaN
+    # embeddings in the padding rows: nothing of the padding may reach a valid row or the cache
+    spec = W.StackSpec("stack-ragged", B=4, L=384, sub_len=128, M=0, n_layers=3, d_model=128, H=2,
+                       dh=64, d_ffn=384, n_scen=8, n_beh=4, seed=33, hist_lens=(384, 77, 300, 129),
+                       cand_counts=(37, 5, 0, 130), nan_padding=True)
+    run(spec, users=(0, 1, 3))
+
+
 def test_small_stack_one_layer_history_output():
     # climber_layer_forward on the history rows: compare the layer output itself
     import torch

@@ -62,6 +62,9 @@ class StackSpec:
     w_std: float = 0.02
     pad_to: int = 128
     seed: int = BASE_SEED
+    hist_lens: tuple = ()      # per-user valid history lengths (default: L for every user)
+    cand_counts: tuple = ()    # per-user candidate counts (default: M for every user)
+    nan_padding: bool = False  # embeddings of the padding rows are NaN: they must never be used
 
 
 CONFIG1 = AttnSpec("cfg1-tiny-f32", "f32", B=1, L=64, sub_len=0, M=8, H=2, dh=32, n_scen=4,
@@ -150,10 +153,12 @@ def make_stack(spec: StackSpec) -> dict:
     rng = _rng(spec.seed)
     d, F = spec.d_model, spec.d_ffn
     assert spec.H * spec.dh == d
-    hist_len = np.full(spec.B, spec.L, dtype=np.int32)
+    hist_len = np.asarray(spec.hist_lens or (spec.L,) * spec.B, dtype=np.int32)
+    n_cand = np.asarray(spec.cand_counts or (spec.M,) * spec.B, dtype=np.int32)
+    assert len(hist_len) == spec.B and len(n_cand) == spec.B
     padded = ((hist_len + spec.pad_to - 1) // spec.pad_to * spec.pad_to).astype(np.int32)
     tok_off = _offsets(padded)
-    cand_off = _offsets(np.full(spec.B, spec.M, dtype=np.int32))
+    cand_off = _offsets(n_cand)
     T, Mt = int(tok_off[-1]), int(cand_off[-1])
     layers = []
     for _ in range(spec.n_layers):
@@ -174,4 +179,7 @@ def make_stack(spec: StackSpec) -> dict:
     w["cbeh"] = rng.integers(0, spec.n_beh, size=Mt).astype(np.int32)
     w["tau"] = rng.uniform(0.5, 2.0, size=(spec.n_layers, spec.n_scen, spec.n_beh)).astype(
         np.float32)
+    if spec.nan_padding:
+        for b in range(spec.B):
+            w["x_hist"][tok_off[b] + hist_len[b]:tok_off[b + 1]] = np.nan
     return w
