@@ -42,7 +42,8 @@
  *  - CLIMBER_BF16: bf16 storage, bf16 MFMA products with fp32 accumulation, fp32
  *    softmax statistics, probabilities rounded to bf16 before the P V product;
  *    requires d_head == 64, padded history lengths that are multiples of 64 and
- *    sub_len == 0 or a multiple of 128; the causal flag is not available.
+ *    sub_len == 0 or a multiple of 128.  Under CLIMBER_HIST_CAUSAL the history pass runs as cache
+ *    write + tiled attention (the one-kernel pass for sub_len 128 / 256 is not causal).
  */
 #ifndef CLIMBER_H
 #define CLIMBER_H

@@ -4,7 +4,7 @@ The binding marshals arguments only; every step of the path runs in the HIP kern
 library.  There is no CPU fallback: using any compute entry point without the built library (or
 without a GPU) raises.
 """
-from .climber import (BF16, F32, MODE_CANDIDATE, MODE_HISTORY, ClimberError, Config, KVCache,
+from .climber import (BF16, F32, HIST_CAUSAL, MODE_CANDIDATE, MODE_HISTORY, ClimberError, Config, KVCache,
                       LayerWeights, climber_attn_history, climber_attn_sumi,
                       climber_history_encode, climber_kv_cache_bytes, climber_kv_cache_create,
                       climber_kv_cache_destroy, climber_kv_cache_rows, climber_layer_forward, climber_probe_mfma,

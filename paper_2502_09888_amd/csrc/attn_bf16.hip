@@ -73,9 +73,10 @@ __device__ __forceinline__ void wait_tiles(int tiles_in_flight)
     }
 }
 
-template <int NW, int QB, bool SUMI>
+template <int NW, int QB, bool SUMI, bool CAUSAL = false>
 __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 {
+    static_assert(!(SUMI && CAUSAL), "the causal flag concerns the history pass");
     static_assert(kStages == 3, "tile t+1 is read while tile t is computed and one more is in flight; "
                                 "every wait in the FAST loop drains all copies");
     constexpr int NT = NW * 64;
@@ -142,7 +143,18 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         }
         k_lo = p.sub_len > 0 ? (q0 / p.sub_len) * p.sub_len : 0;
         k_hi = p.sub_len > 0 ? min(k_lo + p.sub_len, Lb) : Lb;
+        if (CAUSAL) k_hi = min(k_hi, q0 + TQ);  // no query of this tile sees a later key
     }
+    // Causal history pass: token i sees the keys j <= i of its subsequence.  A block of 32 keys is
+    // masked per lane (the lane's queries are q0 + wave*WQ + 32 qb + lane%32) when it reaches up to
+    // or beyond the wave's first query; blocks wholly beyond a wave's queries contribute zeros.
+    int lim[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) lim[qb] = q0 + wave * WQ + qb * 32 + l32 + 1;
+    const int q_wave_lo = q0 + wave * WQ;
+    auto causal = [&](f32x16 (&S)[QB], int blk_lo) __attribute__((always_inline)) {
+        if (CAUSAL && blk_lo + kBlockKeys > q_wave_lo) mask_causal(S, hf, blk_lo, lim);
+    };
     const int n_tiles = (k_hi - k_lo + kTileKeys - 1) / kTileKeys;
     const uint8_t *kv = p.layer_base + ((size_t)t0 * p.H + (size_t)h * Lpad) * (kDHead * 4) +
                         (size_t)(k_lo / kBlockKeys) * kBlockBytes;
@@ -348,6 +360,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         {
             const KFrags k0 = load_k(lds, lane);
             qk_block(st, k0, S0);
+            causal(S0, k_lo);
         }
         // One step = every tile but the last: 64 unmasked keys.  EV numbers the tile that becomes
         // readable in the middle of the step when something rides along with its refill or is
@@ -363,6 +376,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 const VFrags v0 = load_v(cur, lane);
                 __builtin_amdgcn_sched_barrier(0);
                 qk_block(st, k1, S1);
+                causal(S1, k_lo + t * kTileKeys + kBlockKeys);
                 softmax_fast(st, S0, P);
                 pv_block(st, v0, P);
             }
@@ -380,6 +394,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 const VFrags v1 = load_v(cur + kBlockBytes, lane);
                 __builtin_amdgcn_sched_barrier(0);
                 qk_block(st, k0, S0);
+                causal(S0, k_lo + (t + 1) * kTileKeys);
                 softmax_fast(st, S1, P);
                 pv_block(st, v1, P);
             }
@@ -405,6 +420,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             if (two) {
                 const KFrags k1 = load_k(cur + kBlockBytes, lane);
                 qk_block(st, k1, S1);
+                causal(S1, tile_lo + kBlockKeys);
             }
             if (tile_lo + kBlockKeys > k_hi) mask_block(S0, hf, tile_lo, k_hi);
             {
@@ -475,6 +491,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                     const KFrags kf = load_k(cur + blk * kBlockBytes, lane);
                     qk_block(st, kf, S);
                     if (blk_lo + kBlockKeys > k_hi) mask_block(S, hf, blk_lo, k_hi);
+                    causal(S, blk_lo);
                     softmax_safe(st, S, P);
                     const VFrags vf = load_v(cur + blk * kBlockBytes, lane);
                     pv_block(st, vf, P);
@@ -550,7 +567,7 @@ KParams make_params(const AttnArgs &a, int n_qtiles)
     return p;
 }
 
-template <int NW, int QB, bool SUMI>
+template <int NW, int QB, bool SUMI, bool CAUSAL = false>
 hipError_t launch(const AttnArgs &a, hipStream_t s)
 {
     constexpr int TQ = NW * 32 * QB;
@@ -559,7 +576,7 @@ hipError_t launch(const AttnArgs &a, hipStream_t s)
     const int64_t grid = (int64_t)8 * n_qtiles * groups;
     if (grid <= 0 || grid > 0x7fffffff) return hipErrorInvalidValue;
     const KParams p = make_params(a, n_qtiles);
-    hipLaunchKernelGGL((attn_bf16_kernel<NW, QB, SUMI>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<NW, QB, SUMI, CAUSAL>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -599,6 +616,7 @@ hipError_t launch_attn_hist_bf16(const AttnArgs &a, hipStream_t s)
     if (tile == 0) tile = 42;
     const int tq = (tile / 10) * 32 * (tile % 10);
     if (a.sub_len % tq != 0) tile = 41;
+    if (a.causal) return tile == 41 ? launch<4, 1, false, true>(a, s) : launch<4, 2, false, true>(a, s);
     return dispatch<false>(a, tile, s);
 }
 

@@ -104,6 +104,19 @@ static __device__ __forceinline__ void mask_block(f32x16 (&S)[QB], int hf, int b
     }
 }
 
+// causal history attention: the lane's query of block qb sees keys with index < lim[qb] only
+template <int QB>
+static __device__ __forceinline__ void mask_causal(f32x16 (&S)[QB], int hf, int blk_lo, const int (&lim)[QB])
+{
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int kidx = blk_lo + 8 * (r >> 2) + 4 * hf + (r & 3);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+            if (kidx >= lim[qb]) S[qb][r] = -INFINITY;
+    }
+}
+
 // p = exp2(S*scale - sub) rounded to bf16 in B-operand order (P[g] holds the keys of 16-key
 // group g); returns the sum of the values before rounding (round-to-nearest is unbiased, so the
 // denominator and the bf16 numerators agree to well below the bf16 rounding of a single term).

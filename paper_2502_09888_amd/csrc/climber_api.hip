@@ -42,7 +42,6 @@ int check_config(const climber_config *c)
     if (c->flags & ~CLIMBER_HIST_CAUSAL) return CLIMBER_ERR_SHAPE;
     if (c->dtype == CLIMBER_BF16) {
         if (c->d_head != kDHead) return CLIMBER_ERR_UNSUPPORTED;
-        if (c->flags & CLIMBER_HIST_CAUSAL) return CLIMBER_ERR_UNSUPPORTED;
         if (c->sub_len % 128 != 0) return CLIMBER_ERR_ALIGN;
     } else if (c->d_head > 256) {
         return CLIMBER_ERR_UNSUPPORTED;

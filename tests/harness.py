@@ -131,13 +131,14 @@ def stack_config(spec):
     import paper_2502_09888_amd as P
     return P.Config(n_layers=spec.n_layers, d_model=spec.d_model, n_heads=spec.H, d_head=spec.dh,
                     d_ffn=spec.d_ffn, n_scen=spec.n_scen, n_beh=spec.n_beh, sub_len=spec.sub_len,
-                    dtype=P.BF16, qk_scale=spec.qk_scale, rms_eps=spec.rms_eps)
+                    dtype=P.BF16, flags=P.HIST_CAUSAL if spec.causal else 0, qk_scale=spec.qk_scale,
+                    rms_eps=spec.rms_eps)
 
 
 def oracle_stack_config(spec):
     return oracle.StackConfig(spec.n_layers, spec.d_model, spec.H, spec.dh, spec.d_ffn, spec.n_scen,
-                              spec.n_beh, sub_len=spec.sub_len, qk_scale=spec.qk_scale,
-                              rms_eps=spec.rms_eps)
+                              spec.n_beh, sub_len=spec.sub_len, causal=spec.causal,
+                              qk_scale=spec.qk_scale, rms_eps=spec.rms_eps)
 
 
 class GpuStack:

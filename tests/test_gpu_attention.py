@@ -60,6 +60,20 @@ def test_bf16_ragged_lengths_nan_padding():
     check_all(w)
 
 
+def test_bf16_causal_history():
+    # history token i sees j <= i of its subsequence.  Subsequences of 128 and 256 (the query tile of
+    # 256 rows holds two resp. one of them; under the flag they take the tiled kernel, not the
+    # one-kernel pass), one undivided sequence spanning several query tiles, ragged lengths with
+    # NaN padding; the candidate pass on the cache that the causal history call wrote.
+    for name, kw in (("bf16-causal-sub128", dict(B=3, L=384, sub_len=128, M=40, H=2, seed=41)),
+                     ("bf16-causal-sub256", dict(B=2, L=512, sub_len=256, M=40, H=2, seed=42)),
+                     ("bf16-causal-whole", dict(B=2, L=640, sub_len=0, M=33, H=2, seed=43))):
+        check_all(W.make_attention(W.shrink(W.CONFIG2, name=name, **kw)), causal=True)
+    spec = W.shrink(W.CONFIG5, name="bf16-causal-ragged", B=5, L=700, L_min=1, sub_len=256, M=30,
+                    M_min=1, H=2, seed=44)
+    check_all(W.make_attention(spec), causal=True)
+
+
 def test_bf16_single_subsequence_and_odd_lengths():
     spec = W.shrink(W.CONFIG2, name="bf16-onesub", B=2, L=333, L_min=77, sub_len=0, M=70, H=1,
                     nan_padding=True, seed=23)

@@ -42,6 +42,15 @@ def test_small_stack_ragged_lengths_nan_padding():
     run(spec, users=(0, 1, 3))
 
 
+def test_small_stack_causal_history():
+    # weights large enough that attention matters: with these the candidates' outputs of the causal
+    # and the full-visible stack differ by 0.6 (oracle), 30 times the tolerance
+    spec = W.StackSpec("stack-causal", B=2, L=256, sub_len=128, M=50, n_layers=3, d_model=128, H=2,
+                       dh=64, d_ffn=256, n_scen=8, n_beh=4, seed=34, hist_lens=(256, 200), causal=True,
+                       w_std=0.05)
+    run(spec, users=(0, 1))
+
+
 def test_small_stack_one_layer_history_output():
     # climber_layer_forward on the history rows: compare the layer output itself
     import torch

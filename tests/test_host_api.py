@@ -72,7 +72,7 @@ def test_create_rejects_bad_arguments():
     assert create(cfg(qk_scale=0.0), [64], [64]) == -5
     assert create(cfg(qk_scale=float("nan")), [64], [64]) == -5
     assert create(cfg(d_head=32), [64], [64]) == -7           # bf16 path needs d_head 64
-    assert create(cfg(flags=1), [64], [64]) == -7             # causal flag: fp32 path only
+    assert create(cfg(flags=2), [64], [64]) == -2             # unknown flag bit
     assert create(cfg(sub_len=96), [64], [64]) == -3
     assert create(cfg(d_model=100), [64], [64]) == -2
     assert create(cfg(n_scen=0), [64], [64]) == -2

@@ -65,6 +65,7 @@ class StackSpec:
     hist_lens: tuple = ()      # per-user valid history lengths (default: L for every user)
     cand_counts: tuple = ()    # per-user candidate counts (default: M for every user)
     nan_padding: bool = False  # embeddings of the padding rows are NaN: they must never be used
+    causal: bool = False       # history token i sees j <= i of its subsequence only
 
 
 CONFIG1 = AttnSpec("cfg1-tiny-f32", "f32", B=1, L=64, sub_len=0, M=8, H=2, dh=32, n_scen=4,
