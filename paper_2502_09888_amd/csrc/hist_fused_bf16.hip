@@ -3,19 +3,23 @@
 // and kept for the candidates) and the attention inside each subsequence (Sec. 3.1.2 + Eq. (3),
 // one Transformer block per subsequence, per-row temperature) run in ONE kernel.
 //
-// A workgroup (one wave per 32 queries) handles one (user, head, subsequence) at a time.  The subsequence's key and value
-// rows are read from HBM exactly once:
-//   - K rows go HBM -> LDS directly into the MFMA operand fragments the cache stores (the
-//     fragment layout is a permutation of 16-byte row pieces, so the copy only needs the right
-//     global address per lane),
-//   - V rows go HBM -> LDS row-major (XOR-swizzled 16-byte chunks) and are turned into the
-//     transposed, key-permuted V^T fragments with 2-byte LDS gathers, half a subsequence at a time
-//     so that raw rows and fragments share buffers,
-//   - the finished fragments (a contiguous image of the subsequence's cache blocks) are written to
-//     the cache AND consumed in place by the attention of the subsequence's own queries: no ring,
-//     no barrier inside the attention loop, and the cache is never read back.
+// A workgroup (one wave per 32 queries) handles one (user, head, subsequence) at a time.  The
+// subsequence's key and value rows are read from HBM exactly once, HBM -> LDS directly, as whole
+// 128-byte rows (16-byte chunks XOR-swizzled by the row number), and are never rearranged:
+//   - a K operand fragment is a set of 16-byte row pieces: the attention reads it out of the raw
+//     rows with the right address per lane;
+//   - a V^T operand fragment (d along the lanes, keys along the registers) is read out of the raw
+//     rows by the LDS transpose read (ds_read_b64_tr_b16): every lane names 8 bytes of a row, and
+//     within each group of 16 lanes the 4 x 4 blocks of 2-byte elements are exchanged so that a
+//     lane receives 4 consecutive keys of one d;
+//   - every wave reads every block's fragments for its own queries anyway; wave w also writes
+//     piece w of the 8 pieces of a block (4 K fragments, 4 V^T chunks) to the cache from those
+//     registers, so the cache image costs no LDS traffic of its own and is never read back.
+// Rows of the next subsequence travel into the other half of the buffers while this one is
+// attended to: no rearrangement phase, one barrier per subsequence.
 // Slots past a user's valid length hold zeros in the cache and are masked in the softmax whatever
-// the source rows contain; padded query rows produce zeros.
+// the source rows contain (the raw rows are zeroed in LDS after landing); padded query rows
+// produce zeros.
 // The softmax is the FAST / SAFE scheme of attn_bf16.hip (no reference subtraction unless a
 // denominator leaves [1e-12, 1e12]); here the SAFE redo is per wave, since waves share only
 // read-only data.
@@ -60,12 +64,10 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
 {
     static_assert(SUB == 128 || SUB == 256, "fragments of the whole subsequence stay in LDS");
     constexpr int NB = SUB / 32;   // 32-key blocks per subsequence = waves per workgroup
-    constexpr int NT = NB * 64;
-    constexpr int kKraw = 0;            // raw K rows of the subsequence being fetched, NB x 4 KiB
-    constexpr int kVraw = NB * 4096;    // raw V rows, NB x 4 KiB
-    constexpr int kKf = 2 * NB * 4096;  // K fragments of the subsequence being attended to
-    constexpr int kVf = 3 * NB * 4096;  // V^T fragments
-    constexpr int kOut = 4 * NB * 4096; // per wave 4 KiB: query rows in, output rows out
+    constexpr int kBuf = NB * 4096;     // K (or V) rows of one subsequence, 128 B each
+    constexpr int kKraw = 0;            // two buffers of K rows: one attended to, one being fetched
+    constexpr int kVraw = 2 * kBuf;     // two buffers of V rows
+    constexpr int kOut = 4 * kBuf;      // per wave 4 KiB: query rows in, output rows out
     constexpr int kLds = 5 * NB * 4096; // SUB = 256: 160 KiB, one workgroup per CU; 128: 80 KiB, two
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLds];
 
@@ -98,46 +100,140 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
         return item;
     };
     // K and V rows travel HBM -> LDS as whole 128-byte rows (8 lanes per row, so every request is
-    // a full line), chunk c of row r stored at slot c ^ (r & 7).
-    auto issue_kv = [&](const Item &g) __attribute__((always_inline)) {
+    // a full line), chunk c of row r stored at slot c ^ swz(r).  With swz(r) = (r / 2) % 8 both the K
+    // fragment reads (16 consecutive rows, one chunk) and the transpose reads of V (8 rows, 64 bytes
+    // each) spread over all banks.  Wave w fetches rows 32w .. 32w + 31.
+    auto swz = [](int r) __attribute__((always_inline)) { return (r >> 1) & 7; };
+    auto issue_kv_piece = [&](const Item &g, int buf, int i) __attribute__((always_inline)) {
+        const int gi = wave * 4 + i, pos = gi * 64 + lane, r = pos >> 3;
+        const int c = (pos & 7) ^ swz(r);
+        const int64_t off = (g.row0 + min(r, g.n_pad - 1)) * p.ld + g.h * kDHead + c * 8;
+        __builtin_amdgcn_global_load_lds((glb_u8 *)(p.k + off), (lds_u8 *)lds + kKraw + buf * kBuf + gi * 1024, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_u8 *)(p.v + off), (lds_u8 *)lds + kVraw + buf * kBuf + gi * 1024, 16, 0, 0);
+    };
+    auto issue_kv = [&](const Item &g, int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int gi = wave * 4 + i, pos = gi * 64 + lane, r = pos >> 3;
-            const int c = (pos & 7) ^ (r & 7);
-            const int64_t off = (g.row0 + min(r, g.n_pad - 1)) * p.ld + g.h * kDHead + c * 8;
-            __builtin_amdgcn_global_load_lds((glb_u8 *)(p.k + off), (lds_u8 *)lds + kKraw + gi * 1024, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((glb_u8 *)(p.v + off), (lds_u8 *)lds + kVraw + gi * 1024, 16, 0, 0);
+        for (int i = 0; i < 4; ++i) issue_kv_piece(g, buf, i);
+    };
+    // fragments of 32-key block blk out of the raw rows
+    // (Both kinds of fragment reads are written as inline assembly: the compiler cannot tell the rows
+    // being read from the rows a copy in flight is writing -- the other buffer half -- and would wait
+    // for all copies (vmcnt(0)) before every read, i.e. undo the prefetch.  Its own count of LDS
+    // operations in flight does not include these reads, which only makes its waits stricter (LDS
+    // operations return in order); the results are valid after the explicit wait.)
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    struct KRaw { u32x4 x[4]; };
+    struct VRaw { s16x4 h[2][2][2]; };
+    auto read_k = [&](const uint8_t *kraw, int blk, KRaw &k) __attribute__((always_inline)) {
+        const int r = 32 * blk + l32;
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            const uint32_t src = (uint32_t)(uintptr_t)(lds_u8 *)(kraw + r * 128 + (((2 * s4 + hf) ^ swz(r)) * 16));
+            asm volatile("ds_read_b128 %0, %1" : "=v"(k.x[s4]) : "v"(src));
         }
+    };
+    // the K reads have returned although up to BEHIND later LDS reads are still in flight
+    auto done_k = [&](KRaw &k, auto behind_tag) __attribute__((always_inline)) {
+        constexpr int BEHIND = decltype(behind_tag)::value;
+        static_assert(BEHIND == 0 || BEHIND == 8, "");
+        if (BEHIND == 8)
+            asm volatile("s_waitcnt lgkmcnt(8)" : "+v"(k.x[0]), "+v"(k.x[1]), "+v"(k.x[2]), "+v"(k.x[3]));
+        else
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(k.x[0]), "+v"(k.x[1]), "+v"(k.x[2]), "+v"(k.x[3]));
+        KFrags f;
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) f.a[s4] = __builtin_bit_cast(bf16x8, k.x[s4]);
+        return f;
+    };
+    // V^T chunk (gg, db), element e = V[32 blk + 16 gg + 8 (e / 4) + 4 (lane / 32) + e % 4][32 db + lane % 32]:
+    // two transpose reads (e / 4 = 0, 1).  In a group of 16 lanes, lane i receives as element j the
+    // element i % 4 of the 8 bytes named by lane i / 4 + 4 j of the group; so lane 4 j + a of group G
+    // names row .. + j, columns 32 db + 16 (G % 2) + 4 a .. + 3, and lane i ends up with column
+    // 32 db + 16 (G % 2) + i = 32 db + lane % 32 of the rows .. + 0 .. 3.
+    auto read_v = [&](const uint8_t *vraw, int blk, VRaw &v) __attribute__((always_inline)) {
+        const int G = lane >> 4, i16 = lane & 15;
+#pragma unroll
+        for (int gg = 0; gg < 2; ++gg)
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const int r = 32 * blk + 16 * gg + 8 * hh + 4 * (G >> 1) + (i16 >> 2);
+                    const int cb = 64 * db + 32 * (G & 1) + 8 * (i16 & 3);   // byte column of the row
+                    const uint32_t src = (uint32_t)(uintptr_t)(lds_u8 *)(vraw + r * 128 + (((cb >> 4) ^ swz(r)) * 16) + (cb & 15));
+                    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v.h[gg][db][hh]) : "v"(src));
+                }
+    };
+    auto done_v = [&](VRaw &v) __attribute__((always_inline)) {
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(v.h[0][0][0]), "+v"(v.h[0][0][1]), "+v"(v.h[0][1][0]), "+v"(v.h[0][1][1]),
+                       "+v"(v.h[1][0][0]), "+v"(v.h[1][0][1]), "+v"(v.h[1][1][0]), "+v"(v.h[1][1][1]));
+        VFrags f;
+#pragma unroll
+        for (int gg = 0; gg < 2; ++gg)
+#pragma unroll
+            for (int db = 0; db < 2; ++db) {
+                const s16x8 both = __builtin_shufflevector(v.h[gg][db][0], v.h[gg][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                f.a[gg][db] = __builtin_bit_cast(bf16x8, both);
+            }
+        return f;
     };
     struct Rows {  // what a lane fetches ahead for the wave's 32 query rows
         u32x4 q[4];   // piece i: row (i * 64 + lane) / 8 of the wave, 16-byte chunk lane % 8
         int sc, bh;   // ids of row lane % 32
     };
-    auto load_rows = [&](const Item &g, Rows &r) __attribute__((always_inline)) {
-        const int last = max(g.n_valid, 1) - 1;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int id = i * 64 + lane;
-            const int64_t row = g.row0 + min(wave * 32 + (id >> 3), last);
-            r.q[i] = *(const u32x4 *)(p.q + row * p.ld + g.h * kDHead + (id & 7) * 8);
-        }
-        const int64_t row = g.row0 + min(wave * 32 + l32, last);
+    auto load_q_piece = [&](const Item &g, Rows &r, auto i_tag) __attribute__((always_inline)) {
+        constexpr int i = decltype(i_tag)::value;
+        const int id = i * 64 + lane;
+        const int64_t row = g.row0 + min(wave * 32 + (id >> 3), max(g.n_valid, 1) - 1);
+        r.q[i] = *(const u32x4 *)(p.q + row * p.ld + g.h * kDHead + (id & 7) * 8);
+    };
+    auto load_ids = [&](const Item &g, Rows &r) __attribute__((always_inline)) {
+        const int64_t row = g.row0 + min(wave * 32 + l32, max(g.n_valid, 1) - 1);
         r.sc = p.scen[row];
         r.bh = p.beh[row];
     };
+    auto load_rows = [&](const Item &g, Rows &r) __attribute__((always_inline)) {
+        load_q_piece(g, r, std::integral_constant<int, 0>{});
+        load_q_piece(g, r, std::integral_constant<int, 1>{});
+        load_q_piece(g, r, std::integral_constant<int, 2>{});
+        load_q_piece(g, r, std::integral_constant<int, 3>{});
+        load_ids(g, r);
+    };
+    // the temperature table in a register (entry lane % 64), if it has no more than 64 entries: the
+    // per-row lookup is then a cross-lane read instead of a trip to memory at the top of every
+    // subsequence
+    const int n_tau = p.n_scen * p.n_beh;
+    const float tau_reg = n_tau <= 64 ? p.tau[min(lane, n_tau - 1)] : 0.f;
     Item g, gn;
     Rows rows, rows_n;
     int item = next_item(blockIdx.x, g);
     if (item >= p.n_items) return;
     load_rows(g, rows);
-    issue_kv(g);
-    while (true) {
-        uint8_t *kf = lds + kKf;
+    issue_kv(g, 0);
+    // The body exists twice, once per buffer half, so that every LDS offset is a compile-time
+    // constant: the compiler can then see that the rows being read and the rows a copy in flight is
+    // writing are different memory, and does not wait for the copies before each LDS read.
+    auto subsequence = [&](auto buf_tag) __attribute__((always_inline)) -> bool {
+        constexpr int buf = decltype(buf_tag)::value;
+        const uint8_t *kraw = lds + kKraw + buf * kBuf, *vraw = lds + kVraw + buf * kBuf;
         // ---- 1. this subsequence's rows have landed ------------------------------------------
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         const int sc = min(max(rows.sc, 0), p.n_scen - 1);
         const int bhv = min(max(rows.bh, 0), p.n_beh - 1);
-        const float tau_row = p.tau[sc * p.n_beh + bhv];
+        const float tau_row = n_tau <= 64 ? __shfl(tau_reg, sc * p.n_beh + bhv, 64) : p.tau[sc * p.n_beh + bhv];
+        // rows past the valid length become zeros (each wave in the rows it fetched itself)
+        if (g.n_valid < SUB) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int gi = wave * 4 + i, pos = gi * 64 + lane, r = pos >> 3;
+                if (r >= g.n_valid) {
+                    *(u32x4 *)(lds + kKraw + buf * kBuf + pos * 16) = u32x4{0, 0, 0, 0};
+                    *(u32x4 *)(lds + kVraw + buf * kBuf + pos * 16) = u32x4{0, 0, 0, 0};
+                }
+            }
+        }
         // the wave's query rows: through its own staging slice into B-operand order
         uint8_t *tr = lds + kOut + wave * 4096;
 #pragma unroll
@@ -145,62 +241,54 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             const int id = i * 64 + lane, r = id >> 3, c = id & 7;
             *(u32x4 *)(tr + r * 128 + ((c ^ (r & 7)) * 16)) = rows.q[i];
         }
-        __syncthreads();  // every wave's copies are in LDS and every wave is done with the
-                          // previous subsequence (its fragments may be overwritten)
-        // ---- 2. operand fragments; slots past the valid length become zeros.
-        //   K chunk (s, lane)      = K[32kb + lane%32][16s + 8(lane/32) + 0..7]   (16-byte moves)
-        //   V^T chunk (g, db, lane), element e =
-        //                            V[32kb + 16g + 8(e/4) + 4(lane/32) + e%4][32db + lane%32]
-#pragma unroll 1
-        for (int j = 0; j < 4; ++j) {
-            const int pi = j * NT + tid, kb = pi >> 8;
-            {
-                const int s4 = (pi >> 6) & 3, r = 32 * kb + l32, c = 2 * s4 + hf;
-                uint4 kk = *(const uint4 *)(lds + kKraw + r * 128 + ((c ^ (r & 7)) * 16));
-                if (r >= g.n_valid) kk = uint4{0, 0, 0, 0};
-                *(uint4 *)(lds + kKf + pi * 16) = kk;
-            }
-            const int gg = (pi >> 7) & 1, db = (pi >> 6) & 1, d = 32 * db + l32;
-            bf16x8 out;
+        auto read_q = [&](bf16x8 (&q_raw)[4]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int r = 32 * kb + 16 * gg + 8 * (e >> 2) + 4 * hf + (e & 3);
-                const __bf16 x =
-                    *(const __bf16 *)(lds + kVraw + r * 128 + (((d >> 3) ^ (r & 7)) * 16) + (d & 7) * 2);
-                out[e] = r < g.n_valid ? x : (__bf16)0.f;
-            }
-            *(bf16x8 *)(lds + kVf + pi * 16) = out;
-        }
-        bf16x8 q_raw[4];
-#pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4)
-            q_raw[s4] = *(const bf16x8 *)(tr + l32 * 128 + (((2 * s4 + hf) ^ (l32 & 7)) * 16));
-        __syncthreads();  // fragments complete; the raw rows are no longer needed
+            for (int s4 = 0; s4 < 4; ++s4)
+                q_raw[s4] = *(const bf16x8 *)(tr + l32 * 128 + (((2 * s4 + hf) ^ (l32 & 7)) * 16));
+        };
         // the temperature has to be in a register before the next rows are requested: a wait for
         // it placed after those requests would wait for them as well (loads return in order)
         const float c_scale = p.scale_log2e / tau_row;
         asm volatile("" ::"v"(c_scale));
-        // ---- 3. the next subsequence's rows start their way in ------------------------------
+        __syncthreads();  // every wave's rows are in LDS, and every wave is done with the previous
+                          // subsequence: the other buffers may be refilled
+        // ---- 2. the next subsequence's rows start their way in ------------------------------
+        //         piece by piece from inside the attention loop below (a wave that queues all its
+        //         requests at once waits in front of its own MFMAs while the memory pipe takes them)
+        //         The loads into registers (query rows, ids) are not made conditional on there being a
+        //         next subsequence: a conditional load ends in a copy of its result at the join, and
+        //         that copy would wait for the load -- and, completion being in order, for every copy
+        //         issued before it.  After the last subsequence they fetch its own rows once more.
         const int item_n = next_item(item + gridDim.x, gn);
-        if (item_n < p.n_items) {
-            load_rows(gn, rows_n);
-            issue_kv(gn);
-        }
-        // ---- 4. the cache blocks of this subsequence: block kb is written out by all waves, each
-        //         its share, when they reach block kb of the attention loop below, so the stores
-        //         trickle out during the computation instead of arriving as one burst (all
-        //         workgroups of the chip run these phases at about the same time) -------------
+        const bool more = item_n < p.n_items;
+        if (!more) gn = g;
+        load_ids(gn, rows_n);
+        auto prefetch_piece = [&](auto i_tag) __attribute__((always_inline)) {
+            if (more) issue_kv_piece(gn, buf ^ 1, decltype(i_tag)::value);
+            load_q_piece(gn, rows_n, i_tag);
+        };
+        // ---- 3. the cache blocks of this subsequence: 8 pieces of 1 KiB per block (K fragments
+        //         s = 0 .. 3, then V^T chunks (gg, db)), piece w (NB = 4: w and w + 4) written by wave w
+        //         from the registers it has just filled for its own MFMAs ---------------------
         uint8_t *cache_dst = p.layer_base + ((size_t)g.t0 * p.H + (size_t)g.h * g.Lpad) * (kDHead * 4) +
                              (size_t)(g.k_lo / kBlockKeys) * kBlockBytes;
         const int nb_pad = g.n_pad / kBlockKeys;
-        auto store_block = [&](int kb) __attribute__((always_inline)) {
-            // 8 KiB = 512 pieces of 16 B: K fragments then V^T fragments
-#pragma unroll
-            for (int j = 0; j < 512 / NT; ++j) {
-                const int pc = j * NT + tid;
-                const int off = (pc < 256 ? kKf : kVf - 4096) + kb * 4096 + pc * 16;
-                *(u32x4 *)(cache_dst + (size_t)kb * kBlockBytes + pc * 16) = *(const u32x4 *)(lds + off);
-            }
+        const int wv = __builtin_amdgcn_readfirstlane(wave);
+        auto put = [&](int kb, int piece, const bf16x8 &x) __attribute__((always_inline)) {
+            *(u32x4 *)(cache_dst + (size_t)kb * kBlockBytes + (piece * 64 + lane) * 16) = __builtin_bit_cast(u32x4, x);
+        };
+        auto store_k = [&](int kb, const KFrags &f) __attribute__((always_inline)) {
+            if (wv == 0) put(kb, 0, f.a[0]);
+            else if (wv == 1) put(kb, 1, f.a[1]);
+            else if (wv == 2) put(kb, 2, f.a[2]);
+            else if (wv == 3) put(kb, 3, f.a[3]);
+        };
+        auto store_v = [&](int kb, const VFrags &f) __attribute__((always_inline)) {
+            const int w4 = NB == 8 ? wv - 4 : wv;
+            if (w4 == 0) put(kb, 4, f.a[0][0]);
+            else if (w4 == 1) put(kb, 5, f.a[0][1]);
+            else if (w4 == 2) put(kb, 6, f.a[1][0]);
+            else if (w4 == 3) put(kb, 7, f.a[1][1]);
         };
         // ---- 5. attention of the subsequence's own queries, 32 per wave ----------------------
         QState<1> st;
@@ -215,37 +303,80 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             for (int db = 0; db < 2; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) st.O[db][0][r] = 0.f;
-            if (n_blk > 0) qk_block(st, load_k(kf, lane), S0);
+            if (n_blk > 0) {
+                KRaw kr;
+                read_k(kraw, 0, kr);
+                const KFrags k0 = done_k(kr, std::integral_constant<int, 0>{});
+                qk_block(st, k0, S0);
+                if (!SAFE) store_k(0, k0);
+            }
+            // One block: its V^T fragments and the next block's K fragments are requested first; the
+            // next block's logits (MFMA) and this block's exponentials (vector unit) then run while
+            // the V^T reads are still on their way.
             auto block = [&](int blk, f32x16 (&Sc)[1], f32x16 (&Sn)[1]) __attribute__((always_inline)) {
-                if (blk + 1 < n_blk) qk_block(st, load_k(kf + (blk + 1) * 4096, lane), Sn);
+                KRaw kr;
+                VRaw vr;
+                const bool next = blk + 1 < n_blk;
+                if (next) read_k(kraw, blk + 1, kr);
+                read_v(vraw, blk, vr);
+                if (next) {
+                    const KFrags kn = done_k(kr, std::integral_constant<int, 8>{});
+                    qk_block(st, kn, Sn);
+                    if (!SAFE) store_k(blk + 1, kn);
+                }
                 if (32 * (blk + 1) > g.n_valid) mask_block(Sc, hf, 32 * blk, g.n_valid);
                 if (SAFE) softmax_safe(st, Sc, P); else softmax_fast(st, Sc, P);
-                VFrags vf;
-#pragma unroll
-                for (int gg = 0; gg < 2; ++gg)
-#pragma unroll
-                    for (int db = 0; db < 2; ++db)
-                        vf.a[gg][db] = *(const bf16x8 *)(lds + kVf + blk * 4096 + ((gg * 2 + db) * 64 + lane) * 16);
+                const VFrags vf = done_v(vr);
                 pv_block(st, vf, P);
-                if (!SAFE) store_block(blk);
+                if (!SAFE) store_v(blk, vf);
             };
-            for (int blk = 0; blk < n_blk; blk += 2) {
-                block(blk, S0, S1);
-                if (blk + 1 < n_blk) block(blk + 1, S1, S0);
+            // two halves with half of the next subsequence's requests ahead of each (a wave that queues
+            // all its requests at once waits in front of its own MFMAs while the memory pipe takes them)
+            if (!SAFE) {
+                prefetch_piece(std::integral_constant<int, 0>{});
+                prefetch_piece(std::integral_constant<int, 1>{});
+                if (NB == 4) {
+                    prefetch_piece(std::integral_constant<int, 2>{});
+                    prefetch_piece(std::integral_constant<int, 3>{});
+                }
+            }
+            constexpr int kHalf = NB == 8 ? NB / 4 : NB / 2;
+#pragma unroll 1
+            for (int b2 = 0; b2 < kHalf; ++b2) {
+                if (2 * b2 < n_blk) block(2 * b2, S0, S1);
+                if (2 * b2 + 1 < n_blk) block(2 * b2 + 1, S1, S0);
+            }
+            if (NB == 8) {
+                if (!SAFE) {
+                    prefetch_piece(std::integral_constant<int, 2>{});
+                    prefetch_piece(std::integral_constant<int, 3>{});
+                }
+#pragma unroll 1
+                for (int b2 = kHalf; b2 < NB / 2; ++b2) {
+                    if (2 * b2 < n_blk) block(2 * b2, S0, S1);
+                    if (2 * b2 + 1 < n_blk) block(2 * b2 + 1, S1, S0);
+                }
             }
         };
         st.c[0] = c_scale;
+        {
+            bf16x8 q_raw[4];
+            read_q(q_raw);
 #pragma unroll
-        for (int s = 0; s < 4; ++s)  // FAST: q' = bf16(q * c)
+            for (int s = 0; s < 4; ++s)  // FAST: q' = bf16(q * c)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) st.qf[0][s][e] = (__bf16)((float)q_raw[s][e] * st.c[0]);
+                for (int e = 0; e < 8; ++e) st.qf[0][s][e] = (__bf16)((float)q_raw[s][e] * st.c[0]);
+        }
         run(std::false_type{});
-        for (int kb = n_blk; kb < nb_pad; ++kb) store_block(kb);  // blocks of padding only: zeros
+        for (int kb = n_blk; kb < nb_pad; ++kb) {  // blocks of padding only: zeros
+            const bf16x8 zero = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+            if (NB == 8) put(kb, wv, zero);
+            else { put(kb, wv, zero); put(kb, wv + 4, zero); }
+        }
         float lt = st.l[0] + xhalf(st.l[0]);
         const bool bad = g.n_valid > 0 && !(lt > kDenomLo && lt < kDenomHi);
         if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // SAFE (rare): unscaled q, running maximum
-#pragma unroll
-            for (int s = 0; s < 4; ++s) st.qf[0][s] = q_raw[s];
+            read_q(st.qf[0]);  // the staging slice still holds the wave's query rows
             run(std::true_type{});
             lt = st.l[0] + xhalf(st.l[0]);
         }
@@ -275,10 +406,13 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
                 }
             }
         }
-        if (item_n >= p.n_items) break;
+        if (item_n >= p.n_items) return false;
         item = item_n;
         g = gn;
         rows = rows_n;
+        return true;
+    };
+    while (subsequence(std::integral_constant<int, 0>{}) && subsequence(std::integral_constant<int, 1>{})) {
     }
 }
 

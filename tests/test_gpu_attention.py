@@ -74,6 +74,17 @@ def test_bf16_causal_history():
     check_all(W.make_attention(spec), causal=True)
 
 
+def test_bf16_large_temperature_table():
+    # more (scenario, behaviour) pairs than a wavefront has lanes: the one-kernel history pass keeps
+    # small tables in a register and reads larger ones from memory
+    spec = W.shrink(W.CONFIG2, name="bf16-tau-128", B=2, L=256, sub_len=128, M=40, H=2, n_scen=16,
+                    n_beh=8, seed=45)
+    check_all(W.make_attention(spec))
+    spec = W.shrink(W.CONFIG2, name="bf16-tau-128-sub256", B=2, L=512, sub_len=256, M=40, H=2, n_scen=16,
+                    n_beh=8, seed=46)
+    check_all(W.make_attention(spec))
+
+
 def test_bf16_single_subsequence_and_odd_lengths():
     spec = W.shrink(W.CONFIG2, name="bf16-onesub", B=2, L=333, L_min=77, sub_len=0, M=70, H=1,
                     nan_padding=True, seed=23)
