@@ -57,8 +57,7 @@ struct Item {
 // Persistent workgroups (SUB/32 waves, one wave per 32 queries) walk over the subsequences
 // blockIdx.x, blockIdx.x + gridDim.x, ...  While a subsequence is attended to, the rows of the
 // next one are already on their way into the second set of buffers, so HBM stays busy through
-// the compute phases: the kernel as a whole is bound by HBM traffic (K, V, Q rows in; cache
-// blocks and outputs out), not by the latency of any one phase.
+// the compute phases and no wave ever waits for rows.
 template <int SUB>
 __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HParams p)
 {
