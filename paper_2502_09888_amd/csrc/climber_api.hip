@@ -11,6 +11,7 @@
 
 #include "internal.h"
 #include "stack.h"
+#include "gemm.h"
 
 using namespace climber;
 
@@ -163,6 +164,44 @@ int attn_history_strided(const climber_config *cfg, const float *tau_layer, cons
     if (fused) return rt(launch_hist_fused_bf16(a, s));
     if (cfg->dtype == CLIMBER_BF16) return rt(launch_attn_hist_bf16(a, s));
     return rt(launch_attn_f32(a, false, cache->rows, s));
+}
+
+int attn_history_cached(const climber_config *cfg, const float *tau_layer, const void *q, int64_t ld_q,
+                        const int32_t *scen, const int32_t *beh, climber_kv_cache *cache, int32_t layer,
+                        void *o, int64_t ld_o, hipStream_t s)
+{
+    if (cfg->dtype != CLIMBER_BF16) return CLIMBER_ERR_UNSUPPORTED;
+    if (cache->rows == 0) return CLIMBER_OK;
+    AttnArgs a = base_args(cfg, cache, layer, tau_layer);
+    a.q = q;
+    a.k_self = nullptr;  // the history pass of the tiled kernel reads keys and values from the cache only
+    a.v_self = nullptr;
+    a.ld_q = ld_q;
+    a.ld_kv = ld_q;
+    a.scen = scen;
+    a.beh = beh;
+    a.o = o;
+    a.ld_o = ld_o;
+    a.max_rows_per_user = cache->max_pad;
+    a.total_q_rows = cache->rows;
+    return rt(launch_attn_hist_bf16(a, s));
+}
+
+bool cache_direct_target(const climber_config *cfg, climber_kv_cache *cache, int32_t layer, QkvToCache *out)
+{
+    // CLIMBER_QKV_DIRECT=0: keys and values go through rows and the cache writer (tuning, testing)
+    static const bool off = [] {
+        const char *e = getenv("CLIMBER_QKV_DIRECT");
+        return e && e[0] == '0';
+    }();
+    if (off || cfg->dtype != CLIMBER_BF16 || cache->uni_pad <= 0 || cache->rows == 0) return false;
+    out->layer_base = view_of(cache, layer).layer_base;
+    out->H = cfg->n_heads;
+    out->l_valid = cache->uni_len;
+    out->l_pad = cache->uni_pad;
+    out->d = cfg->d_model;
+    out->which0 = 0;
+    return true;
 }
 
 int attn_sumi_strided(const climber_config *cfg, const float *tau_layer,

@@ -45,12 +45,23 @@ hipError_t pack_weights(const PackJobs &jobs, hipStream_t s);
 // Used for the FFN hidden (X = d_ffn: with row-major rows a copy would touch 16 rows 4 KiB apart).
 enum { kTiledA = 1, kTiledC = 2 };
 
+// Fused QKV projection of history rows, all users with the same valid / padded history length:
+// output columns [0, d) (queries) go to C as rows of d, columns [d, 2d) and [2d, 3d) (keys, values)
+// straight into the layer's bf16 KV cache as MFMA operand fragments (the layout of internal.h;
+// slots past the valid length as zeros), so that no key / value rows are written and read back.
+// which0 = 1: the weight and N cover the key and value columns only (last layer: no attention).
+struct QkvToCache {         // layer_base == nullptr: plain store
+    uint8_t *layer_base;    // cache payload of the layer
+    int H, l_valid, l_pad;  // heads of 64; every user's valid and padded history length
+    int d, which0;
+};
+
 // C = A W (+ epilogue).  A: bf16 [M][lda], or tiled (kTiledA; lda unused); w_packed from pack_weight;
 // N % 128 == 0, K % 64 == 0.  EPI_STORE_BF16 / EPI_GELU_BF16: C is bf16 [M][ldc] (EPI_GELU_BF16 with
 // kTiledC: tiled, ldc unused).  EPI_RESID_F32: C is fp32, C = acc + resid.
 hipError_t gemm_bf16(int epi, const void *A, int64_t lda, const void *w_packed, int M, int N, int K,
                      void *C, int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &in_norm,
-                     const RowNormOut &out_norm, int tiled, hipStream_t s);
+                     const RowNormOut &out_norm, int tiled, hipStream_t s, const QkvToCache *to_cache = nullptr);
 
 // What the first projection of a stack call needs of its input rows: the sum of squares of every
 // row into ss[row][0] (ss[row][1 .. n_part-1] = 0) and

@@ -128,7 +128,8 @@ __device__ __forceinline__ void wait_vm()
 template <int EPI, int WM, int WN, int kStages>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
     const __bf16 *A, int64_t lda, const __bf16 *Wp, int M, int N, int K, void *C, int64_t ldc,
-    const float *resid, int64_t ldr, const RowNormIn nin, const RowNormOut nout, const int tiled)
+    const float *resid, int64_t ldr, const RowNormIn nin, const RowNormOut nout, const int tiled,
+    const QkvToCache qc)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr int kABytes = BM * BK * 2, kBBytes = BN * BK * 2, kStageBytes = kABytes + kBBytes;
@@ -303,6 +304,18 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
         }
     };
     load_resid(0, rsd[0]);
+    // direct cache write: slots past a user's valid length hold zeros (the position of the 32-row
+    // block inside its user is wave-uniform; only a block that straddles the valid length looks at
+    // the lane's own row)
+    bool zero_row[WM];
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        zero_row[i] = false;
+        if (EPI == EPI_STORE_BF16 && qc.layer_base) {
+            const int pos = __builtin_amdgcn_readfirstlane((m0 + 32 * (WM * wm + i)) % qc.l_pad);
+            zero_row[i] = pos + l32 >= qc.l_valid;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
 #pragma unroll
@@ -320,11 +333,55 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
                         const float x = acc[i][j][4 * g + e] * rs[i];
                         v[e] = (__bf16)(EPI == EPI_GELU_BF16 ? gelu_erf(x) : x);
                     }
+                    if (EPI == EPI_STORE_BF16 && zero_row[i]) v[0] = v[1] = v[2] = v[3] = (__bf16)0.f;
                     *(uint2 *)(tr + l32 * kPitch + col * 2) = *(const uint2 *)v;
                 }
             }
         if (i + 1 < WM) load_resid(i + 1, rsd[(i + 1) & 1]);
         const int row_base = m0 + 32 * (WM * wm + i);
+        if (EPI == EPI_STORE_BF16 && qc.layer_base) {
+            // the wave's 32 x 64 block is one head of the queries, keys or values of 32 tokens of one
+            // user (padded lengths are multiples of 64)
+            static_assert(EPI != EPI_STORE_BF16 || CW == 64, "a wave's block = one head");
+            typedef short s16x4 __attribute__((ext_vector_type(4)));
+            typedef short s16x8 __attribute__((ext_vector_type(8)));
+            const int which = qc.which0 + col_base / qc.d, h = (col_base % qc.d) / 64;
+            if (row_base < M) {
+                const int b = row_base / qc.l_pad, kb = (row_base % qc.l_pad) / 32;
+                uint8_t *blk = qc.layer_base + ((size_t)b * qc.H + h) * (size_t)qc.l_pad * 256 + (size_t)kb * 8192;
+                if (which == 0) {        // query rows
+#pragma unroll
+                    for (int it = 0; it < kIters; ++it) {
+                        const int id = it * 64 + lane, r = id / kChunksPerRow, cc = id % kChunksPerRow;
+                        if (row_base + r < M)
+                            *(uint4 *)((__bf16 *)C + (int64_t)(row_base + r) * ldc + h * 64 + cc * 8) =
+                                *(const uint4 *)(tr + r * kPitch + cc * 16);
+                    }
+                } else if (which == 1) {  // K fragments: chunk (s, lane) = K[lane % 32][16 s + 8 (lane / 32) ..]
+#pragma unroll
+                    for (int s4 = 0; s4 < 4; ++s4)
+                        *(uint4 *)(blk + (s4 * 64 + lane) * 16) = *(const uint4 *)(tr + l32 * kPitch + (2 * s4 + hf) * 16);
+                } else {                  // V^T chunks by LDS transpose reads (see hist_fused_bf16.hip)
+                    const int G = lane >> 4, i16 = lane & 15;
+#pragma unroll
+                    for (int gg = 0; gg < 2; ++gg)
+#pragma unroll
+                        for (int db = 0; db < 2; ++db) {
+                            s16x4 hv[2];
+#pragma unroll
+                            for (int hh = 0; hh < 2; ++hh) {
+                                const int r = 16 * gg + 8 * hh + 4 * (G >> 1) + (i16 >> 2);
+                                const int cb = 64 * db + 32 * (G & 1) + 8 * (i16 & 3);
+                                hv[hh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                    (__attribute__((address_space(3))) s16x4 *)(tr + r * kPitch + cb));
+                            }
+                            const s16x8 both = __builtin_shufflevector(hv[0], hv[1], 0, 1, 2, 3, 4, 5, 6, 7);
+                            *(uint4 *)(blk + 4096 + ((gg * 2 + db) * 64 + lane) * 16) = __builtin_bit_cast(uint4, both);
+                        }
+                }
+            }
+            continue;
+        }
 #pragma unroll
         for (int it = 0; it < kIters; ++it) {
             const int id = it * 64 + lane, r = id / kChunksPerRow, cc = id % kChunksPerRow;
@@ -368,7 +425,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
 template <int EPI, int WM, int WN, int kStages>
 hipError_t launch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, int K, void *C,
                   int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &nin, const RowNormOut &nout,
-                  int tiled, hipStream_t s)
+                  int tiled, const QkvToCache &qc, hipStream_t s)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr size_t lds_bytes = (size_t)kStages * (BM + BN) * BK * 2;
@@ -378,14 +435,14 @@ hipError_t launch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, i
     if (attr != hipSuccess) return attr;
     const dim3 grid((N / BN) * ((M + BM - 1) / BM)), block(256);
     hipLaunchKernelGGL((gemm_bf16_kernel<EPI, WM, WN, kStages>), grid, block, lds_bytes, s, a, lda, w, M, N, K,
-                       C, ldc, resid, ldr, nin, nout, tiled);
+                       C, ldc, resid, ldr, nin, nout, tiled, qc);
     return hipGetLastError();
 }
 
 template <int EPI>
 hipError_t dispatch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, int K, void *C,
                     int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &nin,
-                    const RowNormOut &nout, int tiled, hipStream_t s)
+                    const RowNormOut &nout, int tiled, const QkvToCache &qc, hipStream_t s)
 {
     // CLIMBER_GEMM_TILE=42|22 overrides the choice, for tuning
     static const int forced = [] { const char *e = getenv("CLIMBER_GEMM_TILE"); return e ? atoi(e) : 0; }();
@@ -394,8 +451,8 @@ hipError_t dispatch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N,
         const int64_t mid = (int64_t)(N / 128) * ((M + 255) / 256);
         tile = mid >= 512 ? 42 : 22;
     }
-    if (tile == 42) return launch<EPI, 4, 2, 3>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, s);
-    return launch<EPI, 2, 2, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, s);
+    if (tile == 42) return launch<EPI, 4, 2, 3>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
+    return launch<EPI, 2, 2, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
 }
 
 }  // namespace
@@ -422,16 +479,23 @@ hipError_t pack_weights(const PackJobs &jobs, hipStream_t s)
 
 hipError_t gemm_bf16(int epi, const void *A, int64_t lda, const void *w_packed, int M, int N, int K,
                      void *C, int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &nin,
-                     const RowNormOut &nout, int tiled, hipStream_t s)
+                     const RowNormOut &nout, int tiled, hipStream_t s, const QkvToCache *to_cache)
 {
     if (M <= 0) return hipSuccess;
+    QkvToCache qc{};
+    if (to_cache) {
+        qc = *to_cache;
+        if (epi != EPI_STORE_BF16 || !qc.layer_base || qc.d % 64 != 0 || qc.H * 64 != qc.d || qc.l_pad % 64 != 0 ||
+            qc.l_pad <= 0 || qc.l_valid < 0 || qc.l_valid > qc.l_pad || N != (3 - qc.which0) * qc.d || M % qc.l_pad != 0)
+            return hipErrorInvalidValue;
+    }
     if (N % 128 != 0 || K % 64 != 0) return hipErrorInvalidValue;
     if ((tiled & ~(kTiledA | kTiledC)) || ((tiled & kTiledC) && epi != EPI_GELU_BF16)) return hipErrorInvalidValue;
     const __bf16 *a = (const __bf16 *)A, *w = (const __bf16 *)w_packed;
     switch (epi) {
-    case EPI_STORE_BF16: return dispatch<EPI_STORE_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, s);
-    case EPI_GELU_BF16: return dispatch<EPI_GELU_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, s);
-    case EPI_RESID_F32: return dispatch<EPI_RESID_F32>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, s);
+    case EPI_STORE_BF16: return dispatch<EPI_STORE_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
+    case EPI_GELU_BF16: return dispatch<EPI_GELU_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
+    case EPI_RESID_F32: return dispatch<EPI_RESID_F32>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -18,6 +18,15 @@ int attn_sumi_strided(const climber_config *cfg, const float *tau_layer,
                       const void *v, int64_t ld, const int32_t *cand_off, int32_t m_total,
                       int32_t m_max, const int32_t *cscen, const int32_t *cbeh, void *o,
                       int64_t ld_o, hipStream_t s);
+// History attention over a cache layer whose keys and values are already in place (written by the
+// fused projection's epilogue, see QkvToCache in gemm.h): bf16 path only.
+int attn_history_cached(const climber_config *cfg, const float *tau_layer, const void *q, int64_t ld_q,
+                        const int32_t *scen, const int32_t *beh, climber_kv_cache *cache, int32_t layer,
+                        void *o, int64_t ld_o, hipStream_t s);
+// Where that epilogue has to write: fills layer_base, H, l_valid, l_pad, d and returns true if the
+// cache is bf16 and all its users share one valid / padded history length.
+struct QkvToCache;
+bool cache_direct_target(const climber_config *cfg, climber_kv_cache *cache, int32_t layer, QkvToCache *out);
 int64_t cache_rows(const climber_kv_cache *c);
 int check_stack_call(const climber_config *cfg, const climber_kv_cache *cache, int32_t layer);
 

@@ -121,6 +121,19 @@ int run_layer(const climber_config *cfg, const PackedLayer &pw, const float *tau
     const int d = cfg->d_model, F = cfg->d_ffn, M = (int)rows;
     const RowNormIn nin{ws.ss, d / 64, 1.f / (float)d, cfg->rms_eps}, no_in{nullptr, 0, 0.f, 0.f};
     const RowNormOut nout{ws.ss, ws.xb, d}, no_out{nullptr, nullptr, 0};
+    QkvToCache qc;
+    if (mode == CLIMBER_MODE_HISTORY && cache_direct_target(cfg, cache, layer, &qc)) {
+        // uniform history lengths: the projection's epilogue writes keys and values into the cache as
+        // operand fragments; only the query rows exist as rows (the last layer needs none at all)
+        if (!x_out) {
+            qc.which0 = 1;
+            return rt(gemm_bf16(EPI_STORE_BF16, xb_in, d, pw.wqkv + (size_t)d * d * 2, M, 2 * d, d, ws.qkv, d,
+                                nullptr, 0, nin, no_out, 0, s, &qc));
+        }
+        TRY(rt(gemm_bf16(EPI_STORE_BF16, xb_in, d, pw.wqkv, M, 3 * d, d, ws.qkv, d, nullptr, 0, nin, no_out, 0,
+                         s, &qc)));
+        TRY(attn_history_cached(cfg, tau_layer, ws.qkv, d, scen, beh, cache, layer, ws.o, d, s));
+    } else {
     TRY(rt(gemm_bf16(EPI_STORE_BF16, xb_in, d, pw.wqkv, M, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, nin,
                      no_out, 0, s)));
     const uint8_t *q = ws.qkv, *k = ws.qkv + (size_t)d * 2, *v = ws.qkv + (size_t)2 * d * 2;
@@ -131,6 +144,7 @@ int run_layer(const climber_config *cfg, const PackedLayer &pw, const float *tau
     } else {
         TRY(attn_sumi_strided(cfg, tau_layer, cache, layer, q, k, v, 3 * d, cand_off, m_total, m_max,
                               scen, beh, ws.o, d, s));
+    }
     }
     TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o, d, pw.wo, M, d, d, ws.h32, d, x_in, d, no_in, nout, 0, s)));
     TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xb, d, pw.w1, M, F, d, ws.u, F, nullptr, 0, nin, no_out, kTiledC, s)));

@@ -42,6 +42,16 @@ def test_small_stack_ragged_lengths_nan_padding():
     run(spec, users=(0, 1, 3))
 
 
+def test_small_stack_uniform_partial_lengths():
+    # all users with the same valid length, which ends inside a 32-key block and inside a subsequence:
+    # the path on which the fused projection writes keys and values straight into the cache (slots past
+    # the valid length must come out as zeros although their embeddings are NaN)
+    spec = W.StackSpec("stack-uniform-partial", B=3, L=256, sub_len=128, M=45, n_layers=3, d_model=128,
+                       H=2, dh=64, d_ffn=256, n_scen=8, n_beh=4, seed=35, hist_lens=(203, 203, 203),
+                       nan_padding=True)
+    run(spec, users=(0, 2))
+
+
 def test_small_stack_causal_history():
     # weights large enough that attention matters: with these the candidates' outputs of the causal
     # and the full-visible stack differ by 0.6 (oracle), 30 times the tolerance
@@ -86,3 +96,22 @@ def test_small_stack_one_layer_history_output():
 
 def test_config4_full_size_sampled_users():
     run(W.CONFIG4, users=(0, 31))
+
+
+def test_projection_through_rows_path():
+    # With uniform history lengths the fused projection writes keys and values straight into the
+    # cache; the same cases must hold when they go through rows and the cache writer instead (what
+    # ragged batches take), which the library reads from the environment once per process.
+    import os
+    import subprocess
+    import sys
+    if os.environ.get("CLIMBER_QKV_DIRECT") == "0":
+        pytest.skip("this is the child process")
+    env = dict(os.environ, CLIMBER_QKV_DIRECT="0")
+    here = os.path.dirname(os.path.abspath(__file__))
+    r = subprocess.run([sys.executable, "-u", "-m", "pytest", os.path.join(here, "test_gpu_stack.py"),
+                        "-m", "gpu", "-x", "-q", "-k", "all_users or uniform_partial or causal",
+                        "--timeout", "120", "--timeout-method", "thread"],
+                       env=env, capture_output=True, text=True, timeout=600)
+    say(r.stdout[-1500:])
+    assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-2000:]
