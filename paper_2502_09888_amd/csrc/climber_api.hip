@@ -64,7 +64,13 @@ int64_t check_padded(const climber_config *c, int32_t B, const int32_t *pad)
     return rows;
 }
 
-size_t header_bytes(int32_t B) { return round_up((size_t)(3 * B + 1) * sizeof(int32_t), 256); }
+// descriptor at the head of the device buffer: hist_len[B], tok_off[B+1], order[B] and, on the bf16
+// path (padded lengths are multiples of 64), the user of every group of 64 padded rows
+size_t header_bytes(const climber_config *c, int32_t B, int64_t rows)
+{
+    const size_t seg = c->dtype == CLIMBER_BF16 ? (size_t)(rows / 64) : 0;
+    return round_up(((size_t)(3 * B + 1) + seg) * sizeof(int32_t), 256);
+}
 
 bool same_config(const climber_config &a, const climber_config &b)
 {
@@ -79,6 +85,7 @@ CacheView view_of(const climber_kv_cache *k, int layer)
     v.hist_len = hd;
     v.tok_off = hd + k->B;
     v.order = hd + 2 * k->B + 1;
+    v.seg = hd + 3 * k->B + 1;
     v.layer_base = k->dev + k->header_bytes + (size_t)layer * k->layer_bytes;
     v.B = k->B;
     return v;
@@ -194,13 +201,18 @@ bool cache_direct_target(const climber_config *cfg, climber_kv_cache *cache, int
         const char *e = getenv("CLIMBER_QKV_DIRECT");
         return e && e[0] == '0';
     }();
-    if (off || cfg->dtype != CLIMBER_BF16 || cache->uni_pad <= 0 || cache->rows == 0) return false;
-    out->layer_base = view_of(cache, layer).layer_base;
+    if (off || cfg->dtype != CLIMBER_BF16 || cache->rows == 0) return false;
+    const CacheView cv = view_of(cache, layer);
+    out->layer_base = cv.layer_base;
     out->H = cfg->n_heads;
-    out->l_valid = cache->uni_len;
-    out->l_pad = cache->uni_pad;
+    out->l_valid = cache->uni_pad > 0 ? cache->uni_len : 0;
+    out->l_pad = cache->uni_pad > 0 ? cache->uni_pad : 0;   // 0: per-user geometry from the tables
     out->d = cfg->d_model;
     out->which0 = 0;
+    out->seg = cv.seg;
+    out->tok_off = cv.tok_off;
+    out->hist_len = cv.hist_len;
+    out->rows = cache->rows;
     return true;
 }
 
@@ -265,7 +277,7 @@ size_t climber_kv_cache_bytes(const climber_config *cfg, int32_t B, const int32_
     if (check_config(cfg) != CLIMBER_OK || !hist_len_padded) return 0;
     const int64_t rows = check_padded(cfg, B, hist_len_padded);
     if (rows < 0) return 0;
-    return header_bytes(B) +
+    return header_bytes(cfg, B, rows) +
            (size_t)cfg->n_layers * 2 * (size_t)rows * cfg->d_model * elem_size(cfg->dtype);
 }
 
@@ -305,7 +317,7 @@ int climber_kv_cache_create(const climber_config *cfg, int32_t B, const int32_t 
                      [&](int a, int b) { return k->hist_len[a] > k->hist_len[b]; });
     k->dev = (uint8_t *)dev_buf;
     k->bytes = bytes;
-    k->header_bytes = header_bytes(B);
+    k->header_bytes = header_bytes(cfg, B, rows);
     k->layer_bytes = 2 * (size_t)rows * cfg->d_model * elem_size(cfg->dtype);
     k->max_pad = max_pad;
     k->max_len = max_len;
@@ -320,6 +332,8 @@ int climber_kv_cache_create(const climber_config *cfg, int32_t B, const int32_t 
     hd.insert(hd.end(), k->hist_len.begin(), k->hist_len.end());
     hd.insert(hd.end(), k->tok_off.begin(), k->tok_off.end());
     hd.insert(hd.end(), k->order.begin(), k->order.end());
+    if (cfg->dtype == CLIMBER_BF16)
+        for (int b = 0; b < B; ++b) hd.insert(hd.end(), (size_t)(hist_len_padded[b] / 64), b);
     if (hipMemcpy(dev_buf, hd.data(), hd.size() * sizeof(int32_t), hipMemcpyHostToDevice) !=
         hipSuccess) {
         (void)hipGetLastError();

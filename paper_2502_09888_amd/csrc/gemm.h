@@ -45,15 +45,19 @@ hipError_t pack_weights(const PackJobs &jobs, hipStream_t s);
 // Used for the FFN hidden (X = d_ffn: with row-major rows a copy would touch 16 rows 4 KiB apart).
 enum { kTiledA = 1, kTiledC = 2 };
 
-// Fused QKV projection of history rows, all users with the same valid / padded history length:
+// Fused QKV projection of the history rows of a batch (all `rows` padded rows of the cache):
 // output columns [0, d) (queries) go to C as rows of d, columns [d, 2d) and [2d, 3d) (keys, values)
 // straight into the layer's bf16 KV cache as MFMA operand fragments (the layout of internal.h;
-// slots past the valid length as zeros), so that no key / value rows are written and read back.
+// slots past a user's valid length as zeros), so that no key / value rows are written and read back.
 // which0 = 1: the weight and N cover the key and value columns only (last layer: no attention).
+// l_pad > 0: every user has this padded and l_valid valid rows; l_pad == 0: ragged batch, a block of
+// 32 rows finds its user in seg (one entry per 64 rows) and the user's rows in tok_off / hist_len.
 struct QkvToCache {         // layer_base == nullptr: plain store
     uint8_t *layer_base;    // cache payload of the layer
-    int H, l_valid, l_pad;  // heads of 64; every user's valid and padded history length
+    int H, l_valid, l_pad;  // heads of 64; uniform batches: every user's valid and padded length
     int d, which0;
+    const int32_t *seg, *tok_off, *hist_len;  // dev: [rows/64], [B+1], [B]
+    int64_t rows;
 };
 
 // C = A W (+ epilogue).  A: bf16 [M][lda], or tiled (kTiledA; lda unused); w_packed from pack_weight;

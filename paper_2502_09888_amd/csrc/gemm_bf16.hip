@@ -208,6 +208,26 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
         }
     }
 
+    // Direct cache write: the user that block row i of this wave (32 tokens) belongs to -- first
+    // row, padded and valid length -- by arithmetic for uniform batches, from the cache's tables for
+    // ragged ones (wave-uniform loads, requested here and first used in the epilogue).
+    int u_t0[WM], u_lp[WM], u_lv[WM];
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        u_t0[i] = 0, u_lp[i] = 64, u_lv[i] = 0;
+        if (EPI == EPI_STORE_BF16 && qc.layer_base) {
+            const int rb = __builtin_amdgcn_readfirstlane(min(m0 + 32 * (WM * wm + i), M - 32));
+            if (qc.l_pad > 0) {
+                u_t0[i] = rb / qc.l_pad * qc.l_pad, u_lp[i] = qc.l_pad, u_lv[i] = qc.l_valid;
+            } else {
+                const int u = qc.seg[rb >> 6];
+                u_t0[i] = qc.tok_off[u];
+                u_lp[i] = qc.tok_off[u + 1] - u_t0[i];
+                u_lv[i] = qc.hist_len[u];
+            }
+        }
+    }
+
     for (int kt = 0; kt < kStages - 1 && kt < n_kt; ++kt) issue(kt);
     // One k-tile: wait for it, read both halves' fragments, then the MFMAs with the copies of tile
     // kt + kStages - 1 (if PREFETCH) dealt out between them, one copy after every kStep-th MFMA, so
@@ -304,18 +324,12 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
         }
     };
     load_resid(0, rsd[0]);
-    // direct cache write: slots past a user's valid length hold zeros (the position of the 32-row
-    // block inside its user is wave-uniform; only a block that straddles the valid length looks at
-    // the lane's own row)
+    // direct cache write: slots past a user's valid length hold zeros
     bool zero_row[WM];
 #pragma unroll
-    for (int i = 0; i < WM; ++i) {
-        zero_row[i] = false;
-        if (EPI == EPI_STORE_BF16 && qc.layer_base) {
-            const int pos = __builtin_amdgcn_readfirstlane((m0 + 32 * (WM * wm + i)) % qc.l_pad);
-            zero_row[i] = pos + l32 >= qc.l_valid;
-        }
-    }
+    for (int i = 0; i < WM; ++i)
+        zero_row[i] = EPI == EPI_STORE_BF16 && qc.layer_base &&
+                      m0 + 32 * (WM * wm + i) - u_t0[i] + l32 >= u_lv[i];
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
 #pragma unroll
@@ -347,8 +361,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
             typedef short s16x8 __attribute__((ext_vector_type(8)));
             const int which = qc.which0 + col_base / qc.d, h = (col_base % qc.d) / 64;
             if (row_base < M) {
-                const int b = row_base / qc.l_pad, kb = (row_base % qc.l_pad) / 32;
-                uint8_t *blk = qc.layer_base + ((size_t)b * qc.H + h) * (size_t)qc.l_pad * 256 + (size_t)kb * 8192;
+                const int kb = (row_base - u_t0[i]) / 32;
+                uint8_t *blk = qc.layer_base + ((size_t)u_t0[i] * qc.H + (size_t)h * u_lp[i]) * 256 + (size_t)kb * 8192;
                 if (which == 0) {        // query rows
 #pragma unroll
                     for (int it = 0; it < kIters; ++it) {
@@ -486,7 +500,9 @@ hipError_t gemm_bf16(int epi, const void *A, int64_t lda, const void *w_packed, 
     if (to_cache) {
         qc = *to_cache;
         if (epi != EPI_STORE_BF16 || !qc.layer_base || qc.d % 64 != 0 || qc.H * 64 != qc.d || qc.l_pad % 64 != 0 ||
-            qc.l_pad <= 0 || qc.l_valid < 0 || qc.l_valid > qc.l_pad || N != (3 - qc.which0) * qc.d || M % qc.l_pad != 0)
+            qc.l_pad < 0 || qc.l_valid < 0 || qc.l_valid > qc.l_pad || N != (3 - qc.which0) * qc.d ||
+            M != qc.rows || M % 64 != 0 || (qc.l_pad > 0 && M % qc.l_pad != 0) ||
+            (qc.l_pad == 0 && (!qc.seg || !qc.tok_off || !qc.hist_len)))
             return hipErrorInvalidValue;
     }
     if (N % 128 != 0 || K % 64 != 0) return hipErrorInvalidValue;

@@ -24,6 +24,7 @@ struct CacheView {          // device-side view of one cache
     const int32_t *hist_len; // [B]
     const int32_t *tok_off;  // [B+1] padded row offsets
     const int32_t *order;    // [B] users by decreasing history length
+    const int32_t *seg;      // bf16: [rows/64] user of every group of 64 padded rows
     uint8_t *layer_base;     // payload of the selected layer
     int B;
 };

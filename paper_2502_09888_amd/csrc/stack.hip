@@ -123,8 +123,8 @@ int run_layer(const climber_config *cfg, const PackedLayer &pw, const float *tau
     const RowNormOut nout{ws.ss, ws.xb, d}, no_out{nullptr, nullptr, 0};
     QkvToCache qc;
     if (mode == CLIMBER_MODE_HISTORY && cache_direct_target(cfg, cache, layer, &qc)) {
-        // uniform history lengths: the projection's epilogue writes keys and values into the cache as
-        // operand fragments; only the query rows exist as rows (the last layer needs none at all)
+        // the projection's epilogue writes keys and values into the cache as operand fragments; only
+        // the query rows exist as rows (the last layer needs none at all)
         if (!x_out) {
             qc.which0 = 1;
             return rt(gemm_bf16(EPI_STORE_BF16, xb_in, d, pw.wqkv + (size_t)d * d * 2, M, 2 * d, d, ws.qkv, d,
@@ -134,17 +134,17 @@ int run_layer(const climber_config *cfg, const PackedLayer &pw, const float *tau
                          s, &qc)));
         TRY(attn_history_cached(cfg, tau_layer, ws.qkv, d, scen, beh, cache, layer, ws.o, d, s));
     } else {
-    TRY(rt(gemm_bf16(EPI_STORE_BF16, xb_in, d, pw.wqkv, M, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, nin,
-                     no_out, 0, s)));
-    const uint8_t *q = ws.qkv, *k = ws.qkv + (size_t)d * 2, *v = ws.qkv + (size_t)2 * d * 2;
-    if (mode == CLIMBER_MODE_HISTORY) {
-        TRY(attn_history_strided(cfg, tau_layer, q, k, v, 3 * d, scen, beh, cache, layer,
-                                 x_out ? ws.o : nullptr, d, s));
-        if (!x_out) return CLIMBER_OK;
-    } else {
-        TRY(attn_sumi_strided(cfg, tau_layer, cache, layer, q, k, v, 3 * d, cand_off, m_total, m_max,
-                              scen, beh, ws.o, d, s));
-    }
+        TRY(rt(gemm_bf16(EPI_STORE_BF16, xb_in, d, pw.wqkv, M, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, nin,
+                         no_out, 0, s)));
+        const uint8_t *q = ws.qkv, *k = ws.qkv + (size_t)d * 2, *v = ws.qkv + (size_t)2 * d * 2;
+        if (mode == CLIMBER_MODE_HISTORY) {
+            TRY(attn_history_strided(cfg, tau_layer, q, k, v, 3 * d, scen, beh, cache, layer,
+                                     x_out ? ws.o : nullptr, d, s));
+            if (!x_out) return CLIMBER_OK;
+        } else {
+            TRY(attn_sumi_strided(cfg, tau_layer, cache, layer, q, k, v, 3 * d, cand_off, m_total, m_max,
+                                  scen, beh, ws.o, d, s));
+        }
     }
     TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o, d, pw.wo, M, d, d, ws.h32, d, x_in, d, no_in, nout, 0, s)));
     TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xb, d, pw.w1, M, F, d, ws.u, F, nullptr, 0, nin, no_out, kTiledC, s)));

@@ -42,6 +42,17 @@ def test_small_stack_ragged_lengths_nan_padding():
     run(spec, users=(0, 1, 3))
 
 
+def test_small_stack_ragged_lengths_padded_to_64():
+    # padded lengths that are odd multiples of 64 (a GEMM wave's 128 rows then hold tokens of up to
+    # three users), one user with no history at all (its candidates see only themselves), a batch
+    # whose row count is not a multiple of the GEMM tile; NaN embeddings in the padding
+    spec = W.StackSpec("stack-ragged-64", B=6, L=0, sub_len=128, M=0, n_layers=3, d_model=128, H=2,
+                       dh=64, d_ffn=256, n_scen=8, n_beh=4, seed=36, pad_to=64,
+                       hist_lens=(40, 0, 64, 200, 130, 33), cand_counts=(20, 7, 3, 40, 0, 11),
+                       nan_padding=True)
+    run(spec, users=(0, 1, 2, 3, 5))
+
+
 def test_small_stack_uniform_partial_lengths():
     # all users with the same valid length, which ends inside a 32-key block and inside a subsequence:
     # the path on which the fused projection writes keys and values straight into the cache (slots past
@@ -99,9 +110,9 @@ def test_config4_full_size_sampled_users():
 
 
 def test_projection_through_rows_path():
-    # With uniform history lengths the fused projection writes keys and values straight into the
-    # cache; the same cases must hold when they go through rows and the cache writer instead (what
-    # ragged batches take), which the library reads from the environment once per process.
+    # The fused projection writes keys and values straight into the cache; the same cases must hold
+    # when they go through rows and the cache writer (or the one-kernel history pass) instead, which
+    # the library reads from the environment once per process.
     import os
     import subprocess
     import sys
@@ -110,7 +121,7 @@ def test_projection_through_rows_path():
     env = dict(os.environ, CLIMBER_QKV_DIRECT="0")
     here = os.path.dirname(os.path.abspath(__file__))
     r = subprocess.run([sys.executable, "-u", "-m", "pytest", os.path.join(here, "test_gpu_stack.py"),
-                        "-m", "gpu", "-x", "-q", "-k", "all_users or uniform_partial or causal",
+                        "-m", "gpu", "-x", "-q", "-k", "all_users or uniform_partial or causal or ragged",
                         "--timeout", "120", "--timeout-method", "thread"],
                        env=env, capture_output=True, text=True, timeout=600)
     say(r.stdout[-1500:])

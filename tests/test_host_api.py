@@ -61,8 +61,9 @@ def test_strerror_names_every_code():
 
 def test_cache_bytes():
     c = cfg()
-    # header + 2 (K,V) * rows * d_model * 2 bytes
-    assert P.climber_kv_cache_bytes(c, [512] * 32) == 512 + 2 * 32 * 512 * 256 * 2
+    # header (lengths, offsets, order: 3 B + 1 words; the user of every 64 rows: rows / 64 words;
+    # rounded up to 256 bytes) + 2 (K,V) * rows * d_model * 2 bytes
+    assert P.climber_kv_cache_bytes(c, [512] * 32) == 1536 + 2 * 32 * 512 * 256 * 2
     assert P.climber_kv_cache_bytes(c, [100]) == 0            # bf16 padding rule
     assert P.climber_kv_cache_bytes(cfg(d_head=32), [128]) == 0
     assert P.climber_kv_cache_bytes(cfg(dtype=P.F32, d_head=32, sub_len=7), [100]) > 0
