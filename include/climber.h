@@ -102,6 +102,10 @@ typedef struct climber_layer_weights {
 typedef struct climber_weights {
     int32_t n_layers;                    /* must equal config.n_layers */
     const climber_layer_weights *layers; /* host array of n_layers entries */
+    const void *packed;                  /* dev, or NULL.  The buffer climber_pack_weights filled from
+                                            these weights: climber_history_encode / climber_sumi_score
+                                            then read it (and never `layers`, which may be NULL)
+                                            instead of repacking the weights on every call. */
 } climber_weights;
 
 /* Opaque host-side handle describing a KV cache that lives in a caller-owned device buffer. */
@@ -185,6 +189,18 @@ int climber_layer_forward(const climber_config *cfg, const climber_layer_weights
                           const int32_t *scen, const int32_t *beh, const int32_t *cand_off,
                           int32_t m_total, int32_t m_max, void *workspace, size_t ws_bytes,
                           void *stream);
+
+/* The projections read their weights as MFMA operand fragments with the RMSNorm gains multiplied
+ * in (f_QKV / f_FFN of Eq. (3)); the stack calls bring `layers` into that form in their workspace
+ * on every call (~1 % of a step).  A caller whose weights do not change can do it once:
+ * climber_pack_weights fills `packed` (dev, 256-byte aligned, >= climber_packed_weights_bytes(cfg),
+ * 0 on an invalid config) from weights->layers on `stream`; the caller then sets weights->packed
+ * to that buffer, which must stay unchanged while calls that were given it are running.  Results
+ * are bitwise the same either way.  Errors: CLIMBER_ERR_NULL, _SHAPE (n_layers), _ALIGN,
+ * _BUFSIZE, _UNSUPPORTED (not the bf16 stack), _RUNTIME. */
+size_t climber_packed_weights_bytes(const climber_config *cfg);
+int climber_pack_weights(const climber_config *cfg, const climber_weights *weights, void *packed,
+                         size_t bytes, void *stream);
 
 /* History encode (first phase of the serving flow, Sec. 3.2): runs the packed history embeddings
  * x_hist (dev bf16 [rows][d_model]) through all layers and fills every layer of the cache.  The

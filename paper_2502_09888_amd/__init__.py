@@ -7,7 +7,8 @@ without a GPU) raises.
 from .climber import (BF16, F32, HIST_CAUSAL, MODE_CANDIDATE, MODE_HISTORY, ClimberError, Config, KVCache,
                       LayerWeights, climber_attn_history, climber_attn_sumi,
                       climber_history_encode, climber_kv_cache_bytes, climber_kv_cache_create,
-                      climber_kv_cache_destroy, climber_kv_cache_rows, climber_layer_forward, climber_probe_mfma,
+                      climber_kv_cache_destroy, climber_kv_cache_rows, climber_layer_forward, climber_pack_weights,
+                      climber_packed_weights_bytes, climber_probe_mfma,
                       climber_strerror, climber_sumi_score, climber_workspace_bytes, library_path,
                       load_library)
 

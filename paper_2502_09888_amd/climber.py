@@ -39,7 +39,7 @@ class LayerWeights(C.Structure):
 
 
 class _Weights(C.Structure):
-    _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(LayerWeights))]
+    _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(LayerWeights)), ("packed", C.c_void_p)]
 
 
 _lib = None
@@ -79,6 +79,10 @@ def load_library():
     lib.climber_probe_mfma.argtypes = [i32, i32, vp, vp]
     lib.climber_workspace_bytes.restype = sz
     lib.climber_workspace_bytes.argtypes = [cfgp, i64]
+    lib.climber_packed_weights_bytes.restype = sz
+    lib.climber_packed_weights_bytes.argtypes = [cfgp]
+    lib.climber_pack_weights.restype = C.c_int
+    lib.climber_pack_weights.argtypes = [cfgp, C.POINTER(_Weights), vp, sz, vp]
     lib.climber_layer_forward.restype = C.c_int
     lib.climber_layer_forward.argtypes = [cfgp, C.POINTER(LayerWeights), vp, i32, i32, vp, vp, vp,
                                           vp, vp, vp, i32, i32, vp, sz, vp]
@@ -196,9 +200,22 @@ def _layer_struct(lw) -> LayerWeights:
     return LayerWeights(*[_ptr(lw[n]) for n in ("g1", "wqkv", "wo", "g2", "w1", "w2")])
 
 
-def _weights_struct(layers):
+def _weights_struct(layers, packed=None):
     arr = (LayerWeights * len(layers))(*[_layer_struct(l) for l in layers])
-    return _Weights(len(layers), arr), arr
+    return _Weights(len(layers), arr, _ptr(packed)), arr
+
+
+def climber_packed_weights_bytes(cfg: Config) -> int:
+    return int(load_library().climber_packed_weights_bytes(C.byref(cfg)))
+
+
+def climber_pack_weights(cfg: Config, layers, packed, stream=None) -> None:
+    """Bring the weights into the form the projections read, once; pass the buffer as `packed` to
+    climber_history_encode / climber_sumi_score."""
+    w, keep = _weights_struct(layers)
+    _ok(load_library().climber_pack_weights(C.byref(cfg), C.byref(w), _ptr(packed),
+                                            packed.numel() * packed.element_size(), _stream(stream)),
+        "climber_pack_weights")
 
 
 def climber_layer_forward(cfg: Config, layer_weights, tau_layer, layer: int, mode: int,
@@ -212,8 +229,8 @@ def climber_layer_forward(cfg: Config, layer_weights, tau_layer, layer: int, mod
 
 
 def climber_history_encode(cfg: Config, layers, tau, x_hist, scen, beh, cache: KVCache, workspace,
-                           stream=None) -> None:
-    w, keep = _weights_struct(layers)
+                           stream=None, packed=None) -> None:
+    w, keep = _weights_struct(layers, packed)
     _ok(load_library().climber_history_encode(
         C.byref(cfg), C.byref(w), _ptr(tau), _ptr(x_hist), _ptr(scen), _ptr(beh), cache.handle,
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
@@ -221,8 +238,8 @@ def climber_history_encode(cfg: Config, layers, tau, x_hist, scen, beh, cache: K
 
 
 def climber_sumi_score(cfg: Config, layers, tau, cache: KVCache, x_cand, cand_off, m_total: int,
-                       m_max: int, cand_scen, cand_beh, y_cand, workspace, stream=None) -> None:
-    w, keep = _weights_struct(layers)
+                       m_max: int, cand_scen, cand_beh, y_cand, workspace, stream=None, packed=None) -> None:
+    w, keep = _weights_struct(layers, packed)
     _ok(load_library().climber_sumi_score(
         C.byref(cfg), C.byref(w), _ptr(tau), cache.handle, _ptr(x_cand), _ptr(cand_off), m_total,
         m_max, _ptr(cand_scen), _ptr(cand_beh), _ptr(y_cand), _ptr(workspace),

@@ -162,6 +162,27 @@ int check_layer_weights(const climber_layer_weights *w)
     return CLIMBER_OK;
 }
 
+// weights of a whole-stack call: either prepacked (weights->packed) or per-layer pointers
+int check_weights(const climber_config *cfg, const climber_weights *weights)
+{
+    if (!weights) return CLIMBER_ERR_NULL;
+    if (weights->n_layers != cfg->n_layers) return CLIMBER_ERR_SHAPE;
+    if (weights->packed) return (uintptr_t)weights->packed % 256 == 0 ? CLIMBER_OK : CLIMBER_ERR_ALIGN;
+    if (!weights->layers) return CLIMBER_ERR_NULL;
+    for (int l = 0; l < cfg->n_layers; ++l) TRY(check_layer_weights(&weights->layers[l]));
+    return CLIMBER_OK;
+}
+
+// packed weights in place for the call: the caller's buffer, or the workspace's after one launch
+int stage_weights(const climber_config *cfg, const climber_weights *weights, Workspace &ws, hipStream_t s)
+{
+    if (weights->packed) {
+        ws.wpack = (uint8_t *)const_cast<void *>(weights->packed);
+        return CLIMBER_OK;
+    }
+    return pack_layers(cfg, weights->layers, cfg->n_layers, ws, s);
+}
+
 int check_cand_args(const climber_config *cfg, const int32_t *cand_off, int32_t m_total, int32_t m_max)
 {
     if (!cand_off) return CLIMBER_ERR_NULL;
@@ -180,6 +201,27 @@ size_t climber_workspace_bytes(const climber_config *cfg, int64_t max_rows)
 {
     if (check_stack_config(cfg) != CLIMBER_OK || max_rows < 0) return 0;
     return carve(cfg, max_rows, nullptr).total;
+}
+
+size_t climber_packed_weights_bytes(const climber_config *cfg)
+{
+    if (check_stack_config(cfg) != CLIMBER_OK || cfg->n_layers < 1) return 0;
+    return carve(cfg, 0, nullptr).wlayer * (size_t)cfg->n_layers;
+}
+
+int climber_pack_weights(const climber_config *cfg, const climber_weights *weights, void *packed,
+                         size_t bytes, void *stream)
+{
+    TRY(check_stack_config(cfg));
+    if (cfg->n_layers < 1) return CLIMBER_ERR_SHAPE;
+    if (!weights || !weights->layers || !packed) return CLIMBER_ERR_NULL;
+    if (weights->n_layers != cfg->n_layers) return CLIMBER_ERR_SHAPE;
+    for (int l = 0; l < cfg->n_layers; ++l) TRY(check_layer_weights(&weights->layers[l]));
+    if ((uintptr_t)packed % 256 != 0) return CLIMBER_ERR_ALIGN;
+    if (bytes < climber_packed_weights_bytes(cfg)) return CLIMBER_ERR_BUFSIZE;
+    Workspace ws = carve(cfg, 0, nullptr);
+    ws.wpack = (uint8_t *)packed;
+    return pack_layers(cfg, weights->layers, cfg->n_layers, ws, (hipStream_t)stream);
 }
 
 int climber_layer_forward(const climber_config *cfg, const climber_layer_weights *w,
@@ -220,19 +262,17 @@ int climber_history_encode(const climber_config *cfg, const climber_weights *wei
 {
     TRY(check_stack_config(cfg));
     TRY(check_stack_call(cfg, cache, 0));
-    if (!weights || !weights->layers || !tau || !x_hist || !scen || !beh || !workspace)
-        return CLIMBER_ERR_NULL;
-    if (weights->n_layers != cfg->n_layers) return CLIMBER_ERR_SHAPE;
-    for (int l = 0; l < cfg->n_layers; ++l) TRY(check_layer_weights(&weights->layers[l]));
+    if (!tau || !x_hist || !scen || !beh || !workspace) return CLIMBER_ERR_NULL;
+    TRY(check_weights(cfg, weights));
     const int64_t rows = cache_rows(cache);
     if (rows * (int64_t)std::max(cfg->d_ffn, 3 * cfg->d_model) >= (int64_t)1 << 31)
         return CLIMBER_ERR_RANGE;
     if ((uintptr_t)workspace % 256 != 0 || (uintptr_t)x_hist % 16 != 0) return CLIMBER_ERR_ALIGN;
-    const Workspace ws = carve(cfg, rows, workspace);
+    Workspace ws = carve(cfg, rows, workspace);
     if (ws_bytes < ws.total) return CLIMBER_ERR_BUFSIZE;
     if (rows == 0) return CLIMBER_OK;
     hipStream_t s = (hipStream_t)stream;
-    TRY(pack_layers(cfg, weights->layers, cfg->n_layers, ws, s));
+    TRY(stage_weights(cfg, weights, ws, s));
     TRY(rt(row_prep_bf16(x_hist, ws.x32, ws.ss, cfg->d_model / 64, rows, cfg->d_model, s)));
     const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
     for (int l = 0; l < cfg->n_layers; ++l) {
@@ -252,19 +292,16 @@ int climber_sumi_score(const climber_config *cfg, const climber_weights *weights
 {
     TRY(check_stack_config(cfg));
     TRY(check_stack_call(cfg, cache, 0));
-    if (!weights || !weights->layers || !tau || !x_cand || !cand_scen || !cand_beh || !y_cand ||
-        !workspace)
-        return CLIMBER_ERR_NULL;
-    if (weights->n_layers != cfg->n_layers) return CLIMBER_ERR_SHAPE;
-    for (int l = 0; l < cfg->n_layers; ++l) TRY(check_layer_weights(&weights->layers[l]));
+    if (!tau || !x_cand || !cand_scen || !cand_beh || !y_cand || !workspace) return CLIMBER_ERR_NULL;
+    TRY(check_weights(cfg, weights));
     TRY(check_cand_args(cfg, cand_off, m_total, m_max));
     if ((uintptr_t)workspace % 256 != 0 || (uintptr_t)x_cand % 16 != 0 || (uintptr_t)y_cand % 16 != 0)
         return CLIMBER_ERR_ALIGN;
-    const Workspace ws = carve(cfg, m_total, workspace);
+    Workspace ws = carve(cfg, m_total, workspace);
     if (ws_bytes < ws.total) return CLIMBER_ERR_BUFSIZE;
     if (m_total == 0) return CLIMBER_OK;
     hipStream_t s = (hipStream_t)stream;
-    TRY(pack_layers(cfg, weights->layers, cfg->n_layers, ws, s));
+    TRY(stage_weights(cfg, weights, ws, s));
     TRY(rt(row_prep_bf16(x_cand, ws.x32, ws.ss, cfg->d_model / 64, m_total, cfg->d_model, s)));
     const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
     for (int l = 0; l < cfg->n_layers; ++l) {

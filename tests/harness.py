@@ -168,16 +168,16 @@ class GpuStack:
         self.m_total = int(w["cand_off"][-1])
         self.m_max = int(np.diff(w["cand_off"]).max())
 
-    def encode(self):
+    def encode(self, packed=None):
         self.P.climber_history_encode(self.cfg, self.layers, self.tau, self.x_hist, self.scen,
-                                      self.beh, self.cache, self.ws)
+                                      self.beh, self.cache, self.ws, packed=packed)
 
-    def score(self):
+    def score(self, packed=None):
         t = self.torch
         y = t.full((self.m_total, self.spec.d_model), float("nan"), dtype=t.float32, device="cuda:0")
         self.P.climber_sumi_score(self.cfg, self.layers, self.tau, self.cache, self.x_cand,
                                   self.cand_off, self.m_total, self.m_max, self.cscen, self.cbeh, y,
-                                  self.ws)
+                                  self.ws, packed=packed)
         t.cuda.synchronize()
         return y.cpu().numpy()
 

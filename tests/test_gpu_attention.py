@@ -85,6 +85,23 @@ def test_bf16_large_temperature_table():
     check_all(W.make_attention(spec))
 
 
+def test_bf16_shape_sweep():
+    # seeded sweep over shapes the API admits: paddings of 64 and 128, subsequence lengths that are
+    # any multiple of 128 (384 takes the tiled kernel with 128-query tiles), 1..3 heads, ragged
+    # histories down to no history at all, candidate counts around the 128 / 256 query tiles and
+    # down to none, both masks, NaN padding
+    rng = np.random.Generator(np.random.Philox(20250209))
+    for i in range(12):
+        sub = int(rng.choice([0, 128, 256, 384, 512]))
+        L = int(rng.integers(1, 900))
+        M = int(rng.choice([1, 31, 127, 128, 129, 255, 257, 300]))
+        spec = W.shrink(W.CONFIG2, name=f"bf16-sweep-{i}", B=int(rng.integers(1, 5)), L=L,
+                        L_min=int(rng.integers(0, L + 1)), sub_len=sub, M=M, M_min=int(rng.integers(0, M + 1)),
+                        H=int(rng.integers(1, 4)), pad_to=int(rng.choice([64, 128])), nan_padding=True,
+                        n_scen=int(rng.integers(1, 9)), n_beh=int(rng.integers(1, 5)), seed=1000 + i)
+        check_all(W.make_attention(spec), causal=bool(rng.integers(0, 2)))
+
+
 def test_bf16_single_subsequence_and_odd_lengths():
     spec = W.shrink(W.CONFIG2, name="bf16-onesub", B=2, L=333, L_min=77, sub_len=0, M=70, H=1,
                     nan_padding=True, seed=23)

@@ -105,6 +105,30 @@ def test_small_stack_one_layer_history_output():
     assert e < 2e-2
 
 
+def test_prepacked_weights_give_the_same_bits():
+    # weights brought into operand order once (climber_pack_weights) instead of on every call
+    import torch
+    spec = W.StackSpec("stack-prepacked", B=2, L=256, sub_len=128, M=70, n_layers=2, d_model=128, H=2,
+                       dh=64, d_ffn=256, n_scen=8, n_beh=4, seed=37, hist_lens=(256, 130))
+    say(f"[case] {spec.name}")
+    w = W.make_stack(spec)
+    g = GpuStack(w)
+    g.encode()
+    y0 = g.score()
+    torch.cuda.synchronize()
+    cache0 = g.buf.clone()
+    payload = spec.n_layers * 2 * int(w["tok_off"][-1]) * spec.d_model * 2
+    packed = torch.empty(g.P.climber_packed_weights_bytes(g.cfg), dtype=torch.uint8, device="cuda")
+    g.P.climber_pack_weights(g.cfg, g.layers, packed)
+    g.buf[g.buf.numel() - payload:].zero_()
+    g.encode(packed=packed)
+    y1 = g.score(packed=packed)
+    assert torch.equal(g.buf, cache0)
+    assert np.array_equal(y0, y1)
+    ref, _ = oracle_stack_users(w, (0, 1))
+    assert max_abs(y1, ref) < 2e-2
+
+
 def test_config4_full_size_sampled_users():
     run(W.CONFIG4, users=(0, 31))
 

@@ -109,6 +109,29 @@ def test_workspace_bytes():
     assert P.climber_workspace_bytes(P.Config(n_heads=8, d_head=64, d_ffn=256, rms_eps=0.0), 10) == 0
 
 
+def test_packed_weights_arguments():
+    lib = P.load_library()
+    c4 = P.Config(n_layers=4, n_heads=8, d_head=64, d_ffn=2048, n_scen=8, n_beh=4, sub_len=256)
+    per_layer = 2 * (4 * 512 * 512 + 2 * 512 * 2048)
+    assert P.climber_packed_weights_bytes(c4) == 4 * per_layer
+    assert P.climber_packed_weights_bytes(cfg(dtype=P.F32, d_head=32, sub_len=0)) == 0
+    from paper_2502_09888_amd.climber import LayerWeights, _Weights
+    layers = (LayerWeights * 4)(*[LayerWeights(*([FAKE] * 6)) for _ in range(4)])
+    w = _Weights(4, layers, None)
+    pack = lambda wts, buf, n: lib.climber_pack_weights(C.byref(c4), C.byref(wts) if wts else None, buf, n, None)
+    assert pack(None, FAKE, 1 << 40) == -1
+    assert pack(w, None, 1 << 40) == -1
+    assert pack(_Weights(4, None, None), FAKE, 1 << 40) == -1
+    assert pack(_Weights(3, layers, None), FAKE, 1 << 40) == -2
+    assert pack(w, FAKE + 16, 1 << 40) == -3
+    assert pack(w, FAKE, 4 * per_layer - 1) == -6
+    bad = (LayerWeights * 4)(*[LayerWeights(*([FAKE] * 5 + [None])) for _ in range(4)])
+    assert pack(_Weights(4, bad, None), FAKE, 1 << 40) == -1
+    # a stack call given a misaligned packed buffer is rejected before anything is launched
+    assert lib.climber_sumi_score(C.byref(c4), C.byref(_Weights(4, None, FAKE + 16)), FAKE, None, FAKE, FAKE,
+                                  8, 8, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) in (-1, -3)
+
+
 def test_binding_has_no_cpu_fallback(monkeypatch, tmp_path):
     # a missing library must fail loudly, not route anywhere else
     from paper_2502_09888_amd import climber as mod
