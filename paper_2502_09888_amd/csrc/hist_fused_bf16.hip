@@ -150,19 +150,27 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
     // element i % 4 of the 8 bytes named by lane i / 4 + 4 j of the group; so lane 4 j + a of group G
     // names row .. + j, columns 32 db + 16 (G % 2) + 4 a .. + 3, and lane i ends up with column
     // 32 db + 16 (G % 2) + i = 32 db + lane % 32 of the rows .. + 0 .. 3.
-    auto read_v = [&](const uint8_t *vraw, int blk, VRaw &v) __attribute__((always_inline)) {
+    // With swz(r) = (r / 2) % 8 the address of read (gg, db, hh) of block blk is
+    //   32 blk * 128 + gg * 2048 + hh * 1024 + (db ^ hh) * 64 + (a term of the lane alone):
+    // the swizzle of row .. + 8 hh + 4 (G / 2) + i16 / 4 is 4 hh + 2 (G / 2) + i16 / 8, the chunk is
+    // 4 db + 2 (G % 2) + (i16 / 2) % 2, and the exclusive or of the two splits into 4 (db ^ hh) and a
+    // lane term.  So the eight reads of a block are one address register and eight immediates (the
+    // compiler, given the expression, recomputes every address with ~20 vector instructions per block).
+    const uint32_t v_lane = [&] {
         const int G = lane >> 4, i16 = lane & 15;
-#pragma unroll
-        for (int gg = 0; gg < 2; ++gg)
-#pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const int r = 32 * blk + 16 * gg + 8 * hh + 4 * (G >> 1) + (i16 >> 2);
-                    const int cb = 64 * db + 32 * (G & 1) + 8 * (i16 & 3);   // byte column of the row
-                    const uint32_t src = (uint32_t)(uintptr_t)(lds_u8 *)(vraw + r * 128 + (((cb >> 4) ^ swz(r)) * 16) + (cb & 15));
-                    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v.h[gg][db][hh]) : "v"(src));
-                }
+        const int x = 2 * (G & 1) + ((i16 >> 1) & 1), y = 2 * (G >> 1) + (i16 >> 3);
+        return (uint32_t)((4 * (G >> 1) + (i16 >> 2)) * 128 + (x ^ y) * 16 + 8 * (i16 & 1));
+    }();
+    auto read_v = [&](const uint8_t *vraw, int blk, VRaw &v) __attribute__((always_inline)) {
+        const uint32_t src = (uint32_t)(uintptr_t)(lds_u8 *)vraw + v_lane + blk * 4096;
+        auto one = [](s16x4 &dst, uint32_t a, auto imm_tag) __attribute__((always_inline)) {
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(a), "n"(decltype(imm_tag)::value));
+        };
+#define CLIMBER_V_READ(gg, db, hh) \
+        one(v.h[gg][db][hh], src, std::integral_constant<int, (gg) * 2048 + (hh) * 1024 + ((db) ^ (hh)) * 64>{})
+        CLIMBER_V_READ(0, 0, 0); CLIMBER_V_READ(0, 0, 1); CLIMBER_V_READ(0, 1, 0); CLIMBER_V_READ(0, 1, 1);
+        CLIMBER_V_READ(1, 0, 0); CLIMBER_V_READ(1, 0, 1); CLIMBER_V_READ(1, 1, 0); CLIMBER_V_READ(1, 1, 1);
+#undef CLIMBER_V_READ
     };
     auto done_v = [&](VRaw &v) __attribute__((always_inline)) {
         asm volatile("s_waitcnt lgkmcnt(0)"
@@ -267,8 +275,9 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             load_q_piece(gn, rows_n, i_tag);
         };
         // ---- 3. the cache blocks of this subsequence: 8 pieces of 1 KiB per block (K fragments
-        //         s = 0 .. 3, then V^T chunks (gg, db)), piece w (NB = 4: w and w + 4) written by wave w
-        //         from the registers it has just filled for its own MFMAs ---------------------
+        //         s = 0 .. 3, then V^T chunks (gg, db)); every wave holds every block's fragments in
+        //         registers at some point, and wave w writes block w from them (a choice by the
+        //         block, not by the piece: no register has to be selected by the wave number) ----
         uint8_t *cache_dst = p.layer_base + ((size_t)g.t0 * p.H + (size_t)g.h * g.Lpad) * (kDHead * 4) +
                              (size_t)(g.k_lo / kBlockKeys) * kBlockBytes;
         const int nb_pad = g.n_pad / kBlockKeys;
@@ -277,17 +286,18 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             *(u32x4 *)(cache_dst + (size_t)kb * kBlockBytes + (piece * 64 + lane) * 16) = __builtin_bit_cast(u32x4, x);
         };
         auto store_k = [&](int kb, const KFrags &f) __attribute__((always_inline)) {
-            if (wv == 0) put(kb, 0, f.a[0]);
-            else if (wv == 1) put(kb, 1, f.a[1]);
-            else if (wv == 2) put(kb, 2, f.a[2]);
-            else if (wv == 3) put(kb, 3, f.a[3]);
+            if (kb == wv) {
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) put(kb, s4, f.a[s4]);
+            }
         };
         auto store_v = [&](int kb, const VFrags &f) __attribute__((always_inline)) {
-            const int w4 = NB == 8 ? wv - 4 : wv;
-            if (w4 == 0) put(kb, 4, f.a[0][0]);
-            else if (w4 == 1) put(kb, 5, f.a[0][1]);
-            else if (w4 == 2) put(kb, 6, f.a[1][0]);
-            else if (w4 == 3) put(kb, 7, f.a[1][1]);
+            if (kb == wv) {
+#pragma unroll
+                for (int gg = 0; gg < 2; ++gg)
+#pragma unroll
+                    for (int db = 0; db < 2; ++db) put(kb, 4 + gg * 2 + db, f.a[gg][db]);
+            }
         };
         // ---- 5. attention of the subsequence's own queries, 32 per wave ----------------------
         QState<1> st;
