@@ -107,8 +107,10 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
         const int gi = wave * 4 + i, pos = gi * 64 + lane, r = pos >> 3;
         const int c = (pos & 7) ^ swz(r);
         const int64_t off = (g.row0 + min(r, g.n_pad - 1)) * p.ld + g.h * kDHead + c * 8;
-        __builtin_amdgcn_global_load_lds((glb_u8 *)(p.k + off), (lds_u8 *)lds + kKraw + buf * kBuf + gi * 1024, 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_u8 *)(p.v + off), (lds_u8 *)lds + kVraw + buf * kBuf + gi * 1024, 16, 0, 0);
+        // read once: non-temporal (aux bit 1), so that the rows do not displace the cache blocks being
+        // written, which the candidate pass reads next, from L2
+        __builtin_amdgcn_global_load_lds((glb_u8 *)(p.k + off), (lds_u8 *)lds + kKraw + buf * kBuf + gi * 1024, 16, 0, 2);
+        __builtin_amdgcn_global_load_lds((glb_u8 *)(p.v + off), (lds_u8 *)lds + kVraw + buf * kBuf + gi * 1024, 16, 0, 2);
     };
     auto issue_kv = [&](const Item &g, int buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -172,8 +174,12 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
         CLIMBER_V_READ(1, 0, 0); CLIMBER_V_READ(1, 0, 1); CLIMBER_V_READ(1, 1, 0); CLIMBER_V_READ(1, 1, 1);
 #undef CLIMBER_V_READ
     };
-    auto done_v = [&](VRaw &v) __attribute__((always_inline)) {
-        asm volatile("s_waitcnt lgkmcnt(0)"
+    // the V reads have returned, although the four K reads requested after them (if k_behind) may
+    // still be in flight.  (One statement carries the registers whatever the case: a result that
+    // came out of two alternative statements would be copied at their join.)
+    auto done_v = [&](VRaw &v, bool k_behind) __attribute__((always_inline)) {
+        if (!k_behind) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(4)"
                      : "+v"(v.h[0][0][0]), "+v"(v.h[0][0][1]), "+v"(v.h[0][1][0]), "+v"(v.h[0][1][1]),
                        "+v"(v.h[1][0][0]), "+v"(v.h[1][0][1]), "+v"(v.h[1][1][0]), "+v"(v.h[1][1][1]));
         VFrags f;
@@ -312,30 +318,31 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             for (int db = 0; db < 2; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) st.O[db][0][r] = 0.f;
+            // K fragments are requested two blocks ahead, V^T fragments at the top of their block: when
+            // a block starts, the next block's K has had a whole block's time to arrive, its logits (MFMA)
+            // and this block's exponentials (vector unit) then run while the V^T reads are on their way.
+            // The K registers are requested again as soon as the MFMAs that read them have been issued.
+            KRaw kr;
             if (n_blk > 0) {
-                KRaw kr;
                 read_k(kraw, 0, kr);
                 const KFrags k0 = done_k(kr, std::integral_constant<int, 0>{});
                 qk_block(st, k0, S0);
                 if (!SAFE) store_k(0, k0);
+                if (n_blk > 1) read_k(kraw, 1, kr);
             }
-            // One block: its V^T fragments and the next block's K fragments are requested first; the
-            // next block's logits (MFMA) and this block's exponentials (vector unit) then run while
-            // the V^T reads are still on their way.
             auto block = [&](int blk, f32x16 (&Sc)[1], f32x16 (&Sn)[1]) __attribute__((always_inline)) {
-                KRaw kr;
                 VRaw vr;
-                const bool next = blk + 1 < n_blk;
-                if (next) read_k(kraw, blk + 1, kr);
+                const bool next = blk + 1 < n_blk, next2 = blk + 2 < n_blk;
                 read_v(vraw, blk, vr);
                 if (next) {
                     const KFrags kn = done_k(kr, std::integral_constant<int, 8>{});
                     qk_block(st, kn, Sn);
                     if (!SAFE) store_k(blk + 1, kn);
+                    if (next2) read_k(kraw, blk + 2, kr);
                 }
                 if (32 * (blk + 1) > g.n_valid) mask_block(Sc, hf, 32 * blk, g.n_valid);
                 if (SAFE) softmax_safe(st, Sc, P); else softmax_fast(st, Sc, P);
-                const VFrags vf = done_v(vr);
+                const VFrags vf = done_v(vr, next2);
                 pv_block(st, vf, P);
                 if (!SAFE) store_v(blk, vf);
             };
