@@ -13,8 +13,8 @@
 //     within each group of 16 lanes the 4 x 4 blocks of 2-byte elements are exchanged so that a
 //     lane receives 4 consecutive keys of one d;
 //   - every wave reads every block's fragments for its own queries anyway; wave w also writes
-//     piece w of the 8 pieces of a block (4 K fragments, 4 V^T chunks) to the cache from those
-//     registers, so the cache image costs no LDS traffic of its own and is never read back.
+//     block w of the subsequence (4 K fragments, 4 V^T chunks) to the cache from those registers,
+//     so the cache image costs no LDS traffic of its own and is never read back.
 // Rows of the next subsequence travel into the other half of the buffers while this one is
 // attended to: no rearrangement phase, one barrier per subsequence.
 // Slots past a user's valid length hold zeros in the cache and are masked in the softmax whatever
