@@ -161,13 +161,15 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 
     // K/V tiles go HBM -> LDS directly (no register staging): every wave copies NPRE slabs of
     // 1 KiB (64 lanes x 16 B) per tile; the LDS image equals the HBM image.
-    auto issue_tile = [&](int t) __attribute__((always_inline)) {
+    // tile t into the ring stage at byte offset `stage` (= (t % kStages) * kTileBytes)
+    auto issue_tile_at = [&](int t, int stage) __attribute__((always_inline)) {
         glb_u8 *src = (glb_u8 *)(kv + (size_t)t * kTileBytes + (size_t)tid * 16);
-        lds_u8 *dst = (lds_u8 *)lds + (t % kStages) * kTileBytes + wave * 1024;
+        lds_u8 *dst = (lds_u8 *)lds + stage + wave * 1024;
 #pragma unroll
         for (int i = 0; i < NPRE; ++i)
             __builtin_amdgcn_global_load_lds(src + i * NT * 16, dst + i * NT * 16, 16, 0, 0);
     };
+    auto issue_tile = [&](int t) __attribute__((always_inline)) { issue_tile_at(t, (t % kStages) * kTileBytes); };
     QState<QB> st;
 
     // FAST start: q' = bf16(q*c) from the raw rows in st.qf, empty state (the candidate's own
@@ -367,10 +369,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         // due afterwards (the own rows of a candidate tile); 0 = plain step.  The steps with
         // events are peeled off the loop: inside it they would make the compiler shuffle the
         // accumulators around the branches.
-        auto tile_step = [&](int t, auto ev_tag) __attribute__((always_inline)) {
+        // The ring stages of tiles t, t + 1 and t + 2 come in as byte offsets that the loop carries
+        // along: derived from t % kStages inside the loop, every fragment address took two vector
+        // additions and its own address register instead of an immediate.
+        auto tile_step = [&](int t, int so_cur, int so_nxt, int so_fill, auto ev_tag) __attribute__((always_inline)) {
             constexpr int EV = decltype(ev_tag)::value;
-            const uint8_t *cur = lds + (t % kStages) * kTileBytes;
-            const uint8_t *nxt = lds + ((t + 1) % kStages) * kTileBytes;
+            const uint8_t *cur = lds + so_cur;
+            const uint8_t *nxt = lds + so_nxt;
             {   // block 0 of tile t: its logits are in S0; start block 1's logits
                 const KFrags k1 = load_k(cur + kBlockBytes, lane);
                 const VFrags v0 = load_v(cur, lane);
@@ -386,7 +391,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             __builtin_amdgcn_s_barrier();
             if (SUMI && EV == 1) issue_rows(p.k_self, p.ld_kv);
             if (SUMI && EV == 3) issue_rows(p.v_self, p.ld_kv);
-            if (t + 2 < n_tiles) issue_tile(t + 2);
+            if (t + 2 < n_tiles) issue_tile_at(t + 2, so_fill);
             if (SUMI && EV == 2) own_k();
             if (SUMI && EV == 4) own_v();
             {   // block 1 of tile t; start block 0 of tile t+1
@@ -399,15 +404,22 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 pv_block(st, v1, P);
             }
         };
+        static_assert(kStages == 3, "stage offsets below are written out for a ring of three");
+        constexpr int T1 = kTileBytes, T2 = 2 * kTileBytes;
         if (n_tiles > 1) {
-            tile_step(0, std::integral_constant<int, 1>{});
+            tile_step(0, 0, T1, T2, std::integral_constant<int, 1>{});
             if (n_tiles > 2) {
-                tile_step(1, std::integral_constant<int, 2>{});
+                tile_step(1, T1, T2, 0, std::integral_constant<int, 2>{});
                 if (n_tiles > 3) {
-                    tile_step(2, std::integral_constant<int, 3>{});
+                    tile_step(2, T2, 0, T1, std::integral_constant<int, 3>{});
                     if (n_tiles > 4) {
-                        tile_step(3, std::integral_constant<int, 4>{});
-                        for (int t = 4; t + 1 < n_tiles; ++t) tile_step(t, std::integral_constant<int, 0>{});
+                        tile_step(3, 0, T1, T2, std::integral_constant<int, 4>{});
+                        int so_cur = T1, so_nxt = T2, so_fill = 0;
+                        for (int t = 4; t + 1 < n_tiles; ++t) {
+                            tile_step(t, so_cur, so_nxt, so_fill, std::integral_constant<int, 0>{});
+                            const int so = so_cur;
+                            so_cur = so_nxt, so_nxt = so_fill, so_fill = so;
+                        }
                     }
                 }
             }
