@@ -137,7 +137,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
     constexpr int NPRE = NA + NB;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the wave number as a scalar: LDS destinations of the copies (M0) are then scalar arithmetic
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hf = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
     // Tile of this workgroup.  Workgroups are dealt to the 8 XCDs round-robin in launch order and
@@ -170,10 +171,11 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
         w_src[j] = (const uint8_t *)Wp +
                    (((int64_t)(n0 / 32 + nbl) * (K / 16) + ksl) * 64 + lane) * 16;
     }
-    // copy c (0 .. NPRE-1) of k-tile kt: NA pieces of the A tile, then NB pieces of the W tile
-    auto issue_one = [&](int kt, auto c_tag) __attribute__((always_inline)) {
+    // copy c (0 .. NPRE-1) of k-tile kt into the ring stage at byte offset `stage`: NA pieces of the
+    // A tile, then NB pieces of the W tile
+    auto issue_one = [&](int kt, int stage, auto c_tag) __attribute__((always_inline)) {
         constexpr int c = decltype(c_tag)::value;
-        lds_u8 *base = (lds_u8 *)lds + (kt % kStages) * kStageBytes;
+        lds_u8 *base = (lds_u8 *)lds + stage;
         if constexpr (c < NA)
             __builtin_amdgcn_global_load_lds((glb_u8 *)(a_src[c] + kt * a_step), base + (wave * NA + c) * 1024, 16, 0, 0);
         else
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
                                              base + kABytes + (wave * NB + (c - NA)) * 1024, 16, 0, 0);
     };
     auto issue = [&](int kt) __attribute__((always_inline)) {
-        static_for<NPRE>([&](auto c) __attribute__((always_inline)) { issue_one(kt, c); });
+        static_for<NPRE>([&](auto c) __attribute__((always_inline)) { issue_one(kt, (kt % kStages) * kStageBytes, c); });
     };
 
     f32x16 acc[WM][WN];
@@ -233,14 +235,17 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
     // kt + kStages - 1 (if PREFETCH) dealt out between them, one copy after every kStep-th MFMA, so
     // that a wave never queues its copies back to back in front of its own MFMAs.
     constexpr int kMfma = 2 * WM * WN, kStep = kMfma / NPRE >= 1 ? kMfma / NPRE : 1;
-    auto k_tile = [&](int kt, auto prefetch_tag) __attribute__((always_inline)) {
+    // The ring stages of tile kt and of the tile to prefetch come in as byte offsets carried by the
+    // loop (derived from kt % kStages in here, every fragment address cost vector additions on the
+    // path from the barrier to the first MFMA instead of being an immediate).
+    auto k_tile = [&](int kt, int st_cur, int st_fill, auto prefetch_tag) __attribute__((always_inline)) {
         constexpr bool PREFETCH = decltype(prefetch_tag)::value;
         const int ahead = min(kt + kStages - 1, n_kt) - (kt + 1);  // tiles that may stay in flight
         if (kStages > 3 && ahead >= 2) wait_vm<(kStages > 3 ? 2 : 1) * NPRE>();
         else if (ahead >= 1) wait_vm<NPRE>();
         else wait_vm<0>();
         __builtin_amdgcn_s_barrier();
-        const uint8_t *sa = lds + (kt % kStages) * kStageBytes;
+        const uint8_t *sa = lds + st_cur;
         const uint8_t *sw = sa + kABytes;
         bf16x8 af[2][WM], bfr[2][WN];
         auto read_frags = [&](auto ks_tag) __attribute__((always_inline)) {
@@ -267,15 +272,20 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
                 __builtin_amdgcn_sched_barrier(0);
             }
             if constexpr (PREFETCH && Ms % kStep == kStep - 1 && Ms / kStep < NPRE) {
-                issue_one(kt + kStages - 1, std::integral_constant<int, Ms / kStep>{});
+                issue_one(kt + kStages - 1, st_fill, std::integral_constant<int, Ms / kStep>{});
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
     };
     {
-        int kt = 0;
-        for (; kt + kStages - 1 < n_kt; ++kt) k_tile(kt, std::true_type{});
-        for (; kt < n_kt; ++kt) k_tile(kt, std::false_type{});
+        constexpr int kRing = kStages * kStageBytes;
+        int kt = 0, st_cur = 0, st_fill = kRing - kStageBytes;   // stage of tile kt, stage of tile kt - 1
+        auto advance = [&]() __attribute__((always_inline)) {
+            st_fill = st_cur;
+            st_cur = st_cur + kStageBytes == kRing ? 0 : st_cur + kStageBytes;
+        };
+        for (; kt + kStages - 1 < n_kt; ++kt, advance()) k_tile(kt, st_cur, st_fill, std::true_type{});
+        for (; kt < n_kt; ++kt, advance()) k_tile(kt, st_cur, st_fill, std::false_type{});
     }
 
     // Epilogue.  The operands were fed as (W fragment, A fragment), so a block accumulator is the
