@@ -85,7 +85,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     constexpr int NPRE = kTileBytes / 16 / NT;
     __shared__ __attribute__((aligned(16))) uint8_t lds[kStages * kTileBytes + TQ * 128];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar
     int l32 = lane & 31;
     const int hf = lane >> 5;
 

@@ -70,7 +70,7 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
     constexpr int kLds = 5 * NB * 4096; // SUB = 256: 160 KiB, one workgroup per CU; 128: 80 KiB, two
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLds];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar
     const int l32 = lane & 31, hf = lane >> 5;
 
     auto geometry = [&](int item, Item &g) __attribute__((always_inline)) -> bool {
