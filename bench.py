@@ -299,6 +299,7 @@ def main():
 
     score_ms = timed(score, args.steps)
     encode_ms = timed(encode, args.steps)
+    hist_bytes = 6 * B * L * H * dh * 2   # q, k, v in; K and V cache blocks and o out; bf16
     score_with(other)
     other_ms = timed(lambda: score_with(other), args.steps)
 
@@ -336,6 +337,12 @@ def main():
                       "single_buffer_set": {"ms_per_step": ms_one_set, "candidates_per_s": cands / (ms_one_set * 1e-3),
                                             "scoring_launch_ms": sumi_ms_one_set},
                       "encode_ms": encode_ms, "score_ms": score_ms,
+                      # the history pass (one kernel: cache write + attention inside the subsequences) moves
+                      # Q, K, V rows in and the cache + the output rows out, each once; it is bound by HBM
+                      "history_pass_roofline": {"bound": "hbm", "bytes_per_launch": hist_bytes,
+                                                "achieved": hist_bytes / (encode_ms * 1e-3) / 1e9,
+                                                "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                                "frac": hist_bytes / (encode_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
                       "score_only_candidates_per_s": cands / (score_ms * 1e-3),
                       "other_variant": {"chunks": other_n, "candidates_per_call_per_user": M // other_n,
                                         "score_ms": other_ms,
