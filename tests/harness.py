@@ -6,8 +6,19 @@ import sys
 
 import numpy as np
 
-import oracle
 import workloads as W
+
+
+class _Oracle:
+    """The oracle package, imported on first use: the device-side helpers of this module are also
+    used where the oracle must not be loaded."""
+
+    def __getattr__(self, name):
+        import oracle as _o
+        return getattr(_o, name)
+
+
+oracle = _Oracle()
 
 
 def say(*a):
