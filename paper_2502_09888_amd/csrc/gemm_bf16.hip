@@ -186,6 +186,10 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
         static_for<NPRE>([&](auto c) __attribute__((always_inline)) { issue_one(kt, (kt % kStages) * kStageBytes, c); });
     };
 
+    // the first tiles start their way in before anything else is set up (accumulators, row
+    // statistics, cache geometry: a microsecond or two that the copies' latency covers)
+    for (int kt = 0; kt < kStages - 1 && kt < n_kt; ++kt) issue(kt);
+
     f32x16 acc[WM][WN];
 #pragma unroll
     for (int i = 0; i < WM; ++i)
@@ -230,7 +234,6 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
         }
     }
 
-    for (int kt = 0; kt < kStages - 1 && kt < n_kt; ++kt) issue(kt);
     // One k-tile: wait for it, read both halves' fragments, then the MFMAs with the copies of tile
     // kt + kStages - 1 (if PREFETCH) dealt out between them, one copy after every kStep-th MFMA, so
     // that a wave never queues its copies back to back in front of its own MFMAs.
