@@ -61,5 +61,24 @@ def build(force: bool = False, verbose: bool = False) -> str:
     return LIB
 
 
+def build_probes() -> list:
+    """Compile the stand-alone measurement programs under probes/ (each to <name>.out beside its
+    source); they are not part of the library."""
+    hipcc = _hipcc()
+    pdir = os.path.join(HERE, "probes")
+    outs = []
+    for name in sorted(f for f in os.listdir(pdir) if f.endswith(".hip")):
+        out = os.path.join(pdir, name.replace(".hip", ".out"))
+        r = subprocess.run([hipcc, *[f for f in FLAGS if f != "-fPIC"], os.path.join(pdir, name), "-o", out],
+                           capture_output=True, text=True)
+        if r.returncode != 0:
+            err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+            raise RuntimeError(f"hipcc failed on probes/{name}:\n{err}")
+        outs.append(out)
+    return outs
+
+
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv, verbose=True))
+    if "--probes" in sys.argv:
+        print("\n".join(build_probes()))
