@@ -8,7 +8,7 @@
 //   - how long an MFMA keeps the SIMD from issuing vector instructions: slots of one MFMA followed
 //     by KV independent v_fma_f32; the time per slot beyond KV times the plain instruction cost is
 //     what the MFMA took from the port (variants: accumulator in VGPRs / AGPRs, rotating / chained,
-//     32x32x16 / 16x16x32).
+//     operands A and B in AGPRs, 32x32x16 / 16x16x32).
 //
 //   hipcc -O3 --offload-arch=gfx950 -Xclang -target-feature -Xclang -packed-fp32-ops \
 //         -o issue_port paper_2502_09888_amd/probes/issue_port.hip && ./issue_port
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void valu_kernel(float *out, unsigned long lon
     if (blockIdx.x == 0 && threadIdx.x == 0) ticks[0] = c1 - c0, ticks[1] = w1 - w0;
 }
 
-enum { M32_VGPR, M32_AGPR, M32_VGPR_CHAINED, M16_VGPR };
+enum { M32_VGPR, M32_AGPR, M32_VGPR_CHAINED, M16_VGPR, M32_AB_AGPR, M32_A_AGPR };
 
 template <int MODE, int KV>
 __global__ __launch_bounds__(256) void mfma_kernel(float *out, unsigned long long *ticks, int iters)
@@ -83,6 +83,8 @@ __global__ __launch_bounds__(256) void mfma_kernel(float *out, unsigned long lon
                 asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(a), "v"(b));
             if (MODE == M32_AGPR) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[j]) : "v"(a), "v"(b));
             if (MODE == M16_VGPR) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acs[j]) : "v"(a), "v"(b));
+            if (MODE == M32_AB_AGPR) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[j]) : "a"(a), "a"(b));
+            if (MODE == M32_A_AGPR) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[j]) : "a"(a), "v"(b));
 #pragma unroll
             for (int k = 0; k < KV; ++k) asm volatile("v_fma_f32 %0, %0, %0, %0" : "+v"(x[(i * KV + k) % 16]));
         }
@@ -173,6 +175,10 @@ int main()
     run_mfma<M32_AGPR, 16>(buf, "32x32x16, AGPR acc");
     run_mfma<M32_VGPR_CHAINED, 12>(buf, "32x32x16, one acc chained");
     run_mfma<M32_VGPR_CHAINED, 16>(buf, "32x32x16, one acc chained");
+    run_mfma<M32_AB_AGPR, 12>(buf, "32x32x16, A and B in AGPRs");
+    run_mfma<M32_AB_AGPR, 16>(buf, "32x32x16, A and B in AGPRs");
+    run_mfma<M32_A_AGPR, 12>(buf, "32x32x16, A in AGPRs");
+    run_mfma<M32_A_AGPR, 16>(buf, "32x32x16, A in AGPRs");
     run_mfma<M16_VGPR, 0>(buf, "16x16x32, VGPR acc");
     run_mfma<M16_VGPR, 8>(buf, "16x16x32, VGPR acc");
     run_mfma<M16_VGPR, 12>(buf, "16x16x32, VGPR acc");
