@@ -27,7 +27,8 @@
  *    the kernels (results for such rows are then those of the clamped id).
  *    Temperatures must be finite and > 0; this is the caller's contract (a
  *    non-positive entry gives unspecified values for the rows that use it, never
- *    an out-of-bounds access).
+ *    an out-of-bounds access).  climber_check_inputs() checks both on the device
+ *    and reports into a caller-owned status word.
  *  - Packed batches: the histories of the B users of a batch are stored back to
  *    back with per-user padded lengths; user b owns rows
  *    tok_off[b] .. tok_off[b] + hist_len_padded[b] - 1 of every per-token array,
@@ -69,6 +70,13 @@ extern "C" {
 #define CLIMBER_BF16 1
 
 #define CLIMBER_HIST_CAUSAL 1 /* flags bit 0: history token i only sees j <= i of its subsequence */
+/* Path selection, results equal to within rounding.  The bf16 history pass has two routes where
+ * sub_len is 128 or 256 and the causal flag is off: one kernel that stores the cache blocks and
+ * attends (default), or cache writer + tiled attention (the route of every other sub_len). */
+#define CLIMBER_HIST_TWO_KERNEL 2 /* flags bit 1: always take the cache writer + tiled attention route */
+/* The stack's fused QKV projection writes history keys / values into the cache from its epilogue
+ * (default), or stores them as rows that the history pass then copies into the cache. */
+#define CLIMBER_QKV_VIA_ROWS 4    /* flags bit 2: keys / values go through rows */
 
 #define CLIMBER_MODE_HISTORY 0
 #define CLIMBER_MODE_CANDIDATE 1
@@ -84,7 +92,7 @@ typedef struct climber_config {
     int32_t n_beh;    /* temperature table columns (behaviours / extraction strategies) */
     int32_t sub_len;  /* subsequence length n_k of Sec. 3.1.2; 0 = one subsequence */
     int32_t dtype;    /* CLIMBER_F32 | CLIMBER_BF16 */
-    int32_t flags;    /* CLIMBER_HIST_CAUSAL */
+    int32_t flags;    /* CLIMBER_HIST_CAUSAL | CLIMBER_HIST_TWO_KERNEL | CLIMBER_QKV_VIA_ROWS */
     float qk_scale;   /* multiplies Q K^T before the temperature divide; Eq. (3) literally = 1 */
     float rms_eps;    /* epsilon of the RMSNorm in the layer stack */
 } climber_config;
@@ -161,8 +169,11 @@ int climber_attn_history(const climber_config *cfg, const float *tau_layer, cons
  *     o_c = softmax over { all hist_len[b] cached history keys of b, c's own key } of
  *           qk_scale <q_c, k> / tau[cscen_c][cbeh_c],   applied to the matching values.
  * q_c, k_c, v_c: dev [m_total][H][d_head]; cand_off: dev int32 [B+1], cand_off[0] = 0,
- * non-decreasing, cand_off[B] = m_total; m_max: host value >= max_b (cand_off[b+1]-cand_off[b])
- * (sizes the launch; a user with more candidates than m_max has the excess left unwritten).
+ * non-decreasing, cand_off[B] = m_total; m_max: host value, must be >= max_b (cand_off[b+1] -
+ * cand_off[b]): it sizes the launch, and m_max * B == m_total tells the library that every user
+ * has exactly m_max candidates.  A smaller m_max breaks the contract (rows may then be left
+ * unwritten or scored against the wrong user's history, never an out-of-bounds access);
+ * climber_check_inputs reports it.
  * cand_scen, cand_beh: dev int32 [m_total].  o_c: dev [m_total][d_model].
  * Scoring a candidate set in chunks = calling this repeatedly on the same (const) cache. */
 int climber_attn_sumi(const climber_config *cfg, const float *tau_layer,
@@ -170,6 +181,30 @@ int climber_attn_sumi(const climber_config *cfg, const float *tau_layer,
                       const void *k_c, const void *v_c, const int32_t *cand_off, int32_t m_total,
                       int32_t m_max, const int32_t *cand_scen, const int32_t *cand_beh, void *o_c,
                       void *stream);
+
+/* ---- debug check of device-resident inputs -----------------------------------------------------
+ * Eq. (3) divides a row's logits by tau[scen][beh]: the ids must lie inside the table and the entry
+ * must be finite and > 0.  Ids, offsets and the table live in device memory, so the compute calls
+ * cannot validate them on the host (they clamp ids and leave the rest to the caller's contract).
+ * This call launches one small kernel on `stream` that reads, inside the given bounds only,
+ *   - history rows (cache != NULL): scen / beh of the valid rows of every user of the cache
+ *     (padding rows may hold anything); cand_off, B_cand, m_max are ignored;
+ *   - candidate rows (cache == NULL): scen / beh [m_total], and, if cand_off != NULL, cand_off
+ *     [B_cand + 1] against the rules of climber_attn_sumi (starts at 0, non-decreasing, ends at
+ *     m_total, every count <= m_max);
+ *   - the entries of tau_layer that the checked rows select;
+ * and ORs CLIMBER_BAD_* bits into *status (dev int32; the caller zeroes it before, and reads it after
+ * synchronising the stream: 0 = nothing found).  The kernel always runs to completion.
+ * Errors: CLIMBER_ERR_NULL, _SHAPE (m_total < 0, B_cand < 1 with cand_off), _RUNTIME. */
+#define CLIMBER_BAD_SCEN 1    /* a scenario id outside [0, n_scen) */
+#define CLIMBER_BAD_BEH 2     /* a behaviour id outside [0, n_beh) */
+#define CLIMBER_BAD_TAU 4     /* a selected temperature is not finite or not > 0 */
+#define CLIMBER_BAD_OFFSETS 8 /* cand_off not 0-based, decreasing somewhere, or not ending at m_total */
+#define CLIMBER_BAD_M_MAX 16  /* a user has more candidates than m_max */
+int climber_check_inputs(const climber_config *cfg, const float *tau_layer, const int32_t *scen,
+                         const int32_t *beh, const climber_kv_cache *cache, int32_t m_total,
+                         const int32_t *cand_off, int32_t B_cand, int32_t m_max, int32_t *status,
+                         void *stream);
 
 /* ---- layer stack (CLIMBER_BF16 only) ---------------------------------------------------------- */
 
@@ -220,17 +255,6 @@ int climber_sumi_score(const climber_config *cfg, const climber_weights *weights
                        int32_t m_total, int32_t m_max, const int32_t *cand_scen,
                        const int32_t *cand_beh, float *y_cand, void *workspace, size_t ws_bytes,
                        void *stream);
-
-/* Measurement aid, not a step of the method: launches `workgroups` workgroups of 4 waves, each wave
- * issuing iters x 4 independent v_mfma_f32_32x32x16_bf16 (2*32*32*16 FLOP each) on register
- * operands (pseudo-random values of unit scale, rotating, so that the operand bits toggle the way
- * they do for real activations: the clock the device sustains depends on that) and nothing else, so that a caller timing the launch obtains the bf16 MFMA rate the
- * device sustains at its own clocks: workgroups*4*iters*4*32768 FLOP per launch.  The roofline of
- * the attention kernels (Eq. (3): S = Q K^T and A V are dense contractions) is quoted against the
- * datasheet peak; this figure says how much of that peak the clocks allow.  sink: device buffer of
- * workgroups*256 floats that receives one value per thread.  Errors: CLIMBER_ERR_NULL,
- * CLIMBER_ERR_SHAPE (workgroups < 1 or > 65536, iters < 4 or not a multiple of 4), CLIMBER_ERR_RUNTIME. */
-int climber_probe_mfma(int32_t workgroups, int32_t iters, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -4,11 +4,11 @@ The binding marshals arguments only; every step of the path runs in the HIP kern
 library.  There is no CPU fallback: using any compute entry point without the built library (or
 without a GPU) raises.
 """
-from .climber import (BF16, F32, HIST_CAUSAL, MODE_CANDIDATE, MODE_HISTORY, ClimberError, Config, KVCache,
-                      LayerWeights, climber_attn_history, climber_attn_sumi,
+from .climber import (BAD_BEH, BAD_M_MAX, BAD_OFFSETS, BAD_SCEN, BAD_TAU, BF16, F32, HIST_CAUSAL, HIST_TWO_KERNEL, QKV_VIA_ROWS, MODE_CANDIDATE, MODE_HISTORY, ClimberError, Config, KVCache,
+                      LayerWeights, climber_attn_history, climber_attn_sumi, climber_check_inputs,
                       climber_history_encode, climber_kv_cache_bytes, climber_kv_cache_create,
                       climber_kv_cache_destroy, climber_kv_cache_rows, climber_layer_forward, climber_pack_weights,
-                      climber_packed_weights_bytes, climber_probe_mfma,
+                      climber_packed_weights_bytes,
                       climber_strerror, climber_sumi_score, climber_workspace_bytes, library_path,
                       load_library)
 

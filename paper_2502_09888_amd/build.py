@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libclimber.so")
 SOURCES = ["climber_api.hip", "attn_bf16.hip", "attn_f32.hip", "kv_cache.hip", "stack.hip",
-           "gemm_bf16.hip", "rowwise.hip", "hist_fused_bf16.hip", "probe.hip"]
+           "gemm_bf16.hip", "rowwise.hip", "hist_fused_bf16.hip", "check.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -61,24 +61,5 @@ def build(force: bool = False, verbose: bool = False) -> str:
     return LIB
 
 
-def build_probes() -> list:
-    """Compile the stand-alone measurement programs under probes/ (each to <name>.out beside its
-    source); they are not part of the library."""
-    hipcc = _hipcc()
-    pdir = os.path.join(HERE, "probes")
-    outs = []
-    for name in sorted(f for f in os.listdir(pdir) if f.endswith(".hip")):
-        out = os.path.join(pdir, name.replace(".hip", ".out"))
-        r = subprocess.run([hipcc, *[f for f in FLAGS if f != "-fPIC"], os.path.join(pdir, name), "-o", out],
-                           capture_output=True, text=True)
-        if r.returncode != 0:
-            err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
-            raise RuntimeError(f"hipcc failed on probes/{name}:\n{err}")
-        outs.append(out)
-    return outs
-
-
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv, verbose=True))
-    if "--probes" in sys.argv:
-        print("\n".join(build_probes()))

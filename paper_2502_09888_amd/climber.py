@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libclimber.so")
 
 F32, BF16 = 0, 1
 MODE_HISTORY, MODE_CANDIDATE = 0, 1
-HIST_CAUSAL = 1
+HIST_CAUSAL, HIST_TWO_KERNEL, QKV_VIA_ROWS = 1, 2, 4
 
 
 class ClimberError(RuntimeError):
@@ -75,8 +75,8 @@ def load_library():
     lib.climber_attn_history.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.climber_attn_sumi.restype = C.c_int
     lib.climber_attn_sumi.argtypes = [cfgp, vp, vp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
-    lib.climber_probe_mfma.restype = C.c_int
-    lib.climber_probe_mfma.argtypes = [i32, i32, vp, vp]
+    lib.climber_check_inputs.restype = C.c_int
+    lib.climber_check_inputs.argtypes = [cfgp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp]
     lib.climber_workspace_bytes.restype = sz
     lib.climber_workspace_bytes.argtypes = [cfgp, i64]
     lib.climber_packed_weights_bytes.restype = sz
@@ -184,10 +184,16 @@ def climber_attn_sumi(cfg: Config, tau_layer, cache: KVCache, layer: int, q_c, k
                                          _stream(stream)), "climber_attn_sumi")
 
 
-def climber_probe_mfma(workgroups: int, iters: int, sink, stream=None) -> None:
-    """MFMA-only probe launch (measurement aid); sink: float32 device tensor of workgroups*256."""
-    _ok(load_library().climber_probe_mfma(workgroups, iters, _ptr(sink), _stream(stream)),
-        "climber_probe_mfma")
+BAD_SCEN, BAD_BEH, BAD_TAU, BAD_OFFSETS, BAD_M_MAX = 1, 2, 4, 8, 16
+
+
+def climber_check_inputs(cfg: Config, tau_layer, scen, beh, cache: Optional[KVCache], m_total: int,
+                         cand_off, B_cand: int, m_max: int, status, stream=None) -> None:
+    """Device-side check of ids / offsets / temperatures; ORs BAD_* bits into status (int32 tensor)."""
+    _ok(load_library().climber_check_inputs(C.byref(cfg), _ptr(tau_layer), _ptr(scen), _ptr(beh),
+                                            cache.handle if cache is not None else None, m_total,
+                                            _ptr(cand_off), B_cand, m_max, _ptr(status),
+                                            _stream(stream)), "climber_check_inputs")
 
 
 def climber_workspace_bytes(cfg: Config, max_rows: int) -> int:

@@ -10,9 +10,10 @@
 //     probabilities leave the S^T accumulator already in the B-operand layout the P V product
 //     needs (the cache stores V with the matching key permutation).
 //   - history K/V tiles of 64 keys are copied HBM -> LDS directly (global_load_lds, no register
-//     staging; the cache is stored as MFMA fragments so the copy is linear) into a ring of 4
-//     buffers, three tiles in flight ahead of the one being computed, and are reused by every
-//     wave, i.e. by the whole query tile.
+//     staging; the cache is stored as MFMA fragments so the copy is linear) into a ring of 3
+//     buffers (the tile being computed, the next one, and the one being refilled) and are reused
+//     by every wave, i.e. by the whole query tile.  Query rows and the candidates' own key / value
+//     rows arrive the same way in a landing buffer behind the ring, one slice per wave.
 //   - FAST pass.  Softmax does not depend on the reference subtracted from the logits as long as
 //     numerator and denominator share it, and fp32 / bf16 carry 8 exponent bits, so for logits of
 //     ordinary size NO reference is needed at all: with the per-row temperature folded into the
@@ -21,15 +22,17 @@
 //     (denominator) -- no row maximum, no subtraction, no rescale of O.  The loop is software
 //     pipelined over 32-key blocks: the S^T MFMAs of block i+1 are issued before the exponentials
 //     of block i, so matrix and vector pipes overlap inside one wave.
-//   - SAFE pass.  If any row's denominator leaves [2^-40, 2^40] (or is not finite) the workgroup
-//     redoes its work with the classical online softmax: unscaled q, fp32 scale
+//   - SAFE pass.  Rounding q' to bf16 costs every logit a relative 2^-9, i.e. an error that grows
+//     with the logit.  If any row's denominator leaves [kDenomLo, kDenomHi] (or is not finite)
+//     the workgroup redoes its work with the classical online softmax: unscaled q, fp32 scale
 //     p = exp2(s*c - m*c), running row maximum (moved when exceeded by 2^8, O and l rescaled).
-//     This covers logits of any size exactly; it is never taken for unit-scale inputs.
+//     This covers logits of any size; it is never taken for unit-scale logits.  The decision is
+//     per workgroup, so a row's rounding depends on whether a neighbour of its tile has large
+//     logits: results are bitwise independent of the other rows only within one mode.
 //   - SUMI: the candidate's own key/value initialise the running state, which is the "+ itself"
 //     term of the mask.
 #include "attn_common.h"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace climber {
@@ -214,7 +217,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                     for (int e = 0; e < 8; ++e) dot += (float)st.qf[qb][s][e] * (float)kk[e];
                 }
             }
-            st.m_ref[qb] = dot + xhalf(dot);  // both halves add the same two numbers
+            // SUMI: the own logit (both halves add the same two numbers).  History pass: no member
+            // of the row is known yet; a reference far below any logit makes the first block's
+            // maximum the reference (0 would leave rows whose logits are all very negative with an
+            // empty sum).  Every row sees a key of its first block, so the reference is finite
+            // before the first exponential.
+            st.m_ref[qb] = SUMI ? dot + xhalf(dot) : kSafeNoRef;
             st.l[qb] = (SUMI && hfs == 0) ? 1.f : 0.f;
             if (SUMI) {
                 const __bf16 *vp = p.v_self + row * p.ld_kv + h * kDHead + 4 * hfs;
@@ -249,10 +257,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     float *tau_lds = (float *)(lds + (kStages - 1) * kTileBytes);
     const int n_tau = p.n_scen * p.n_beh;
     const bool tau_in_lds = n_tau <= kTauLds;
-    // Query rows land in the two ring buffers that hold no tile yet: whole 128-byte rows, copied
+    // Query rows land in the landing buffer behind the ring: whole 128-byte rows, copied
     // HBM -> LDS by the wave that owns them (8 lanes per row, so every request is a full line),
     // 16-byte chunks XOR-swizzled by the row number so that the fragment reads below are
-    // conflict-free.
+    // conflict-free.  A wave only ever touches its own slice of that buffer.
     uint8_t *rows_lds = lds + kStages * kTileBytes + wave * (WQ * 128);
     auto issue_rows = [&](const __bf16 *base, int64_t ld) __attribute__((always_inline)) {
 #pragma unroll
@@ -355,10 +363,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     if (n_tiles > 0) {
         f32x16 S0[QB], S1[QB];
         bf16x8 P[QB][2];
-        // every wave has read its query rows (they share buffers 2 and 3 with tiles 2 and 3)
+        // every wave has looked up its temperatures in the table staged in the last ring stage,
+        // which the first refill (tile 2) overwrites
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        for (int t = 2; t < kStages - 1 && t < n_tiles; ++t) issue_tile(t);
         {
             const KFrags k0 = load_k(lds, lane);
             qk_block(st, k0, S0);
@@ -389,6 +397,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             // drains every copy, own rows included); the own rows ride along with the refill
             wait_tiles<NPRE>(0);
             __builtin_amdgcn_s_barrier();
+            // the landing slice is overwritten: this wave's earlier reads of it must have returned
+            if (SUMI && (EV == 1 || EV == 3)) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             if (SUMI && EV == 1) issue_rows(p.k_self, p.ld_kv);
             if (SUMI && EV == 3) issue_rows(p.v_self, p.ld_kv);
             if (t + 2 < n_tiles) issue_tile_at(t + 2, so_fill);
@@ -480,7 +490,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     // Workgroup-wide OR of `bad` through the (idle) landing buffer: one flag per wave in its own
     // slice, one barrier; the barrier also orders the reuse of the LDS ring below.
     int *flag_lds = (int *)(lds + kStages * kTileBytes);
-    if (lane == 0) flag_lds[wave * (WQ * 32)] = __builtin_amdgcn_ballot_w64(bad) != 0;
+    // (the ballot is taken by the whole wave: inside the branch it would see lane 0 only)
+    const int wave_bad = __builtin_amdgcn_ballot_w64(bad) != 0;
+    if (lane == 0) flag_lds[wave * (WQ * 32)] = wave_bad;
     __syncthreads();
     int any_bad = 0;
 #pragma unroll
@@ -594,42 +606,20 @@ hipError_t launch(const AttnArgs &a, hipStream_t s)
 
 // Query-tile shape: 4 waves x QB blocks of 32 queries per workgroup.  QB = 2 (256 queries) re-reads
 // a head's K/V from L2 half as often and reuses every LDS fragment for two MFMAs; QB = 1 (128
-// queries) keeps two waves per SIMD busy when a head has few queries.  CLIMBER_ATTN_TILE=41|42
-// overrides the choice, for tuning.
-int forced_tile()
-{
-    static const int v = [] {
-        const char *e = getenv("CLIMBER_ATTN_TILE");
-        return e ? atoi(e) : 0;
-    }();
-    return v;
-}
-
-template <bool SUMI>
-hipError_t dispatch(const AttnArgs &a, int tile, hipStream_t s)
-{
-    if (tile == 41) return launch<4, 1, SUMI>(a, s);
-    return launch<4, 2, SUMI>(a, s);
-}
-
+// queries) keeps two waves per SIMD busy when a head has few queries.
 }  // namespace
 
 hipError_t launch_attn_sumi_bf16(const AttnArgs &a, hipStream_t s)
 {
-    int tile = forced_tile();
-    if (tile == 0) tile = a.max_rows_per_user > 128 ? 42 : 41;
-    return dispatch<true>(a, tile, s);
+    return a.max_rows_per_user > 128 ? launch<4, 2, true>(a, s) : launch<4, 1, true>(a, s);
 }
 
 hipError_t launch_attn_hist_bf16(const AttnArgs &a, hipStream_t s)
 {
     // a query tile must lie inside one subsequence (sub_len is 0 or a multiple of 128)
-    int tile = forced_tile();
-    if (tile == 0) tile = 42;
-    const int tq = (tile / 10) * 32 * (tile % 10);
-    if (a.sub_len % tq != 0) tile = 41;
-    if (a.causal) return tile == 41 ? launch<4, 1, false, true>(a, s) : launch<4, 2, false, true>(a, s);
-    return dispatch<false>(a, tile, s);
+    const bool wide = a.sub_len % 256 == 0;
+    if (a.causal) return wide ? launch<4, 2, false, true>(a, s) : launch<4, 1, false, true>(a, s);
+    return wide ? launch<4, 2, false>(a, s) : launch<4, 1, false>(a, s);
 }
 
 }  // namespace climber

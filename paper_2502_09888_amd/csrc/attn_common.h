@@ -17,8 +17,13 @@ typedef __attribute__((address_space(3))) uint8_t lds_u8;
 typedef const __attribute__((address_space(1))) uint8_t glb_u8;
 
 constexpr float kSafeSlack = 8.0f;           // SAFE: exp2-domain slack before the row maximum moves
-constexpr float kDenomHi = 1.0e12f;          // FAST is accepted iff kDenomLo < denominator < kDenomHi
-constexpr float kDenomLo = 1.0e-12f;
+// FAST is accepted iff kDenomLo < denominator < kDenomHi for every row.  The window bounds the
+// largest logit of a row (in log2 units it is at most log2 of the denominator), and with it the
+// error that rounding q * c to bf16 puts on the dominant probabilities; rows beyond it are redone
+// by the SAFE pass, which scales in fp32.
+constexpr float kDenomHi = 1048576.f;        // 2^20
+constexpr float kDenomLo = 1.f / 1048576.f;  // 2^-20
+constexpr float kSafeNoRef = -1.0e30f;       // SAFE: "no reference yet", below any finite logit
 
 // Per-wave softmax state for QB blocks of 32 queries.
 template <int QB>

@@ -40,7 +40,7 @@ int check_config(const climber_config *c)
         return CLIMBER_ERR_SHAPE;
     if (c->dtype != CLIMBER_F32 && c->dtype != CLIMBER_BF16) return CLIMBER_ERR_SHAPE;
     if (!(c->qk_scale > 0.f) || !std::isfinite(c->qk_scale)) return CLIMBER_ERR_TAU;
-    if (c->flags & ~CLIMBER_HIST_CAUSAL) return CLIMBER_ERR_SHAPE;
+    if (c->flags & ~(CLIMBER_HIST_CAUSAL | CLIMBER_HIST_TWO_KERNEL | CLIMBER_QKV_VIA_ROWS)) return CLIMBER_ERR_SHAPE;
     if (c->dtype == CLIMBER_BF16) {
         if (c->d_head != kDHead) return CLIMBER_ERR_UNSUPPORTED;
         if (c->sub_len % 128 != 0) return CLIMBER_ERR_ALIGN;
@@ -126,17 +126,6 @@ int check_cache_use(const climber_config *cfg, const climber_kv_cache *cache, in
 // ---- internal entry points used by the stack driver (stack.hip) ---------------------------------
 namespace climber {
 
-// CLIMBER_HIST_FUSED=0 selects the two-kernel history path (cache writer + ring attention) also
-// where the fused kernel applies; for tuning and for testing both.
-static bool fused_history_disabled()
-{
-    static const bool off = [] {
-        const char *e = getenv("CLIMBER_HIST_FUSED");
-        return e && e[0] == '0';
-    }();
-    return off;
-}
-
 int attn_history_strided(const climber_config *cfg, const float *tau_layer, const void *q,
                          const void *k, const void *v, int64_t ld, const int32_t *scen,
                          const int32_t *beh, climber_kv_cache *cache, int32_t layer, void *o,
@@ -145,7 +134,7 @@ int attn_history_strided(const climber_config *cfg, const float *tau_layer, cons
     const CacheView cv = view_of(cache, layer);
     if (cache->rows == 0) return CLIMBER_OK;
     // short subsequences, bf16: one kernel writes the cache and attends (K/V rows read once)
-    const bool fused = cfg->dtype == CLIMBER_BF16 && o && !fused_history_disabled() &&
+    const bool fused = cfg->dtype == CLIMBER_BF16 && o && !(cfg->flags & CLIMBER_HIST_TWO_KERNEL) &&
                        hist_fused_supported(cfg->sub_len, (cfg->flags & CLIMBER_HIST_CAUSAL) != 0);
     if (fused) {
     } else if (cfg->dtype == CLIMBER_BF16) {
@@ -196,12 +185,7 @@ int attn_history_cached(const climber_config *cfg, const float *tau_layer, const
 
 bool cache_direct_target(const climber_config *cfg, climber_kv_cache *cache, int32_t layer, QkvToCache *out)
 {
-    // CLIMBER_QKV_DIRECT=0: keys and values go through rows and the cache writer (tuning, testing)
-    static const bool off = [] {
-        const char *e = getenv("CLIMBER_QKV_DIRECT");
-        return e && e[0] == '0';
-    }();
-    if (off || cfg->dtype != CLIMBER_BF16 || cache->rows == 0) return false;
+    if ((cfg->flags & CLIMBER_QKV_VIA_ROWS) || cfg->dtype != CLIMBER_BF16 || cache->rows == 0) return false;
     const CacheView cv = view_of(cache, layer);
     out->layer_base = cv.layer_base;
     out->H = cfg->n_heads;
@@ -391,6 +375,25 @@ int climber_attn_sumi(const climber_config *cfg, const float *tau_layer,
     return attn_sumi_strided(cfg, tau_layer, cache, layer, q_c, k_c, v_c, cfg->d_model, cand_off,
                              m_total, m_max, cand_scen, cand_beh, o_c, cfg->d_model,
                              (hipStream_t)stream);
+}
+
+int climber_check_inputs(const climber_config *cfg, const float *tau_layer, const int32_t *scen,
+                         const int32_t *beh, const climber_kv_cache *cache, int32_t m_total,
+                         const int32_t *cand_off, int32_t B_cand, int32_t m_max, int32_t *status,
+                         void *stream)
+{
+    int e = check_config(cfg);
+    if (e) return e;
+    if (!tau_layer || !scen || !beh || !status) return CLIMBER_ERR_NULL;
+    if (cache) {
+        if (!same_config(*cfg, cache->cfg)) return CLIMBER_ERR_SHAPE;
+        const CacheView cv = view_of(cache, 0);
+        return rt(launch_check_inputs(tau_layer, scen, beh, cache->rows, cv.hist_len, cv.tok_off, nullptr,
+                                      cache->B, cfg->n_scen, cfg->n_beh, 0, status, (hipStream_t)stream));
+    }
+    if (m_total < 0 || (cand_off && B_cand < 1)) return CLIMBER_ERR_SHAPE;
+    return rt(launch_check_inputs(tau_layer, scen, beh, m_total, nullptr, nullptr, cand_off, B_cand,
+                                  cfg->n_scen, cfg->n_beh, m_max, status, (hipStream_t)stream));
 }
 
 }  // extern "C"

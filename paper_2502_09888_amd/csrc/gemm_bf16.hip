@@ -471,14 +471,9 @@ hipError_t dispatch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N,
                     int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &nin,
                     const RowNormOut &nout, int tiled, const QkvToCache &qc, hipStream_t s)
 {
-    // CLIMBER_GEMM_TILE=42|22 overrides the choice, for tuning
-    static const int forced = [] { const char *e = getenv("CLIMBER_GEMM_TILE"); return e ? atoi(e) : 0; }();
-    int tile = forced;
-    if (tile == 0) {
-        const int64_t mid = (int64_t)(N / 128) * ((M + 255) / 256);
-        tile = mid >= 512 ? 42 : 22;
-    }
-    if (tile == 42) return launch<EPI, 4, 2, 3>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
+    // macro tile 256 x 128 when that still gives every CU two workgroups, else 128 x 128
+    const int64_t big_tiles = (int64_t)(N / 128) * ((M + 255) / 256);
+    if (big_tiles >= 512) return launch<EPI, 4, 2, 3>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
     return launch<EPI, 2, 2, 4>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
 }
 

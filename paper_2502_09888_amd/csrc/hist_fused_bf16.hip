@@ -313,7 +313,7 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             f32x16 S0[1], S1[1];
             bf16x8 P[1][2];
             st.l[0] = 0.f;
-            st.m_ref[0] = 0.f;
+            st.m_ref[0] = kSafeNoRef;  // SAFE: the first block's maximum becomes the reference
 #pragma unroll
             for (int db = 0; db < 2; ++db)
 #pragma unroll

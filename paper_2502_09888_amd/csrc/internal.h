@@ -64,4 +64,9 @@ hipError_t launch_kv_write_bf16(const CacheView &c, const void *k, const void *v
 hipError_t launch_kv_write_f32(const CacheView &c, const void *k, const void *v, int64_t ld, int H,
                                int d_head, int64_t total_rows, hipStream_t s);
 
+// device-side id / offset / temperature check (check.hip); hist_len / tok_off non-null: history rows
+hipError_t launch_check_inputs(const float *tau, const int32_t *scen, const int32_t *beh, int64_t n_rows,
+                               const int32_t *hist_len, const int32_t *tok_off, const int32_t *cand_off,
+                               int B, int n_scen, int n_beh, int m_max, int32_t *status, hipStream_t s);
+
 }  // namespace climber

@@ -24,7 +24,7 @@ int attn_history_cached(const climber_config *cfg, const float *tau_layer, const
                         const int32_t *scen, const int32_t *beh, climber_kv_cache *cache, int32_t layer,
                         void *o, int64_t ld_o, hipStream_t s);
 // Where that epilogue has to write: fills every field but which0 and returns true if the cache is
-// bf16 and holds rows (CLIMBER_QKV_DIRECT=0 in the environment makes it return false).
+// bf16 and holds rows (the CLIMBER_QKV_VIA_ROWS flag makes it return false).
 struct QkvToCache;
 bool cache_direct_target(const climber_config *cfg, climber_kv_cache *cache, int32_t layer, QkvToCache *out);
 int64_t cache_rows(const climber_kv_cache *c);

@@ -31,24 +31,24 @@ def torch_dtype(spec_dtype):
     return torch.bfloat16 if spec_dtype == "bf16" else torch.float32
 
 
-def make_config(spec, n_layers=1, causal=False):
+def make_config(spec, n_layers=1, causal=False, flags=0):
     import paper_2502_09888_amd as P
     return P.Config(n_layers=n_layers, n_heads=spec.H, d_head=spec.dh, n_scen=spec.n_scen,
                     n_beh=spec.n_beh, sub_len=spec.sub_len,
                     dtype=P.BF16 if spec.dtype == "bf16" else P.F32,
-                    flags=1 if causal else 0, qk_scale=spec.qk_scale)
+                    flags=(P.HIST_CAUSAL if causal else 0) | flags, qk_scale=spec.qk_scale)
 
 
 class GpuAttention:
     """Device copies of one attention workload + a KV cache created for it."""
 
-    def __init__(self, w, causal=False):
+    def __init__(self, w, causal=False, flags=0):
         import torch
         import paper_2502_09888_amd as P
         self.P, self.torch, self.w = P, torch, w
         spec = w["spec"]
         self.spec = spec
-        self.cfg = make_config(spec, causal=causal)
+        self.cfg = make_config(spec, causal=causal, flags=flags)
         dt = torch_dtype(spec.dtype)
         dev = "cuda:0"
         self.dt = dt
@@ -137,13 +137,43 @@ def max_abs(a, b):
     return float(np.max(np.abs(np.asarray(a, np.float64) - np.asarray(b, np.float64)))) if a.size else 0.0
 
 
+def decode_bf16_cache(buf, B, tok_off, H, n_layers=1):
+    """Turn the bf16 KV cache (the layout documented with the cache geometry of the library: per
+    layer and (user, head), blocks of 32 keys = 4 KiB of K operand fragments + 4 KiB of V^T operand
+    fragments with the key order inside a 16-key group permuted) back into K, V arrays
+    [n_layers, T_pad, H, 64] (float32).  buf: the cache's device buffer as a numpy uint8 array.
+    Index arithmetic only."""
+    import torch
+    T = int(tok_off[-1])
+    header = ((3 * B + 1 + T // 64) * 4 + 255) // 256 * 256
+    layer_bytes = 2 * T * H * 64 * 2
+    K = np.zeros((n_layers, T, H, 64), np.float32)
+    V = np.zeros((n_layers, T, H, 64), np.float32)
+    for l in range(n_layers):
+        raw = buf[header + l * layer_bytes: header + (l + 1) * layer_bytes]
+        vals = torch.from_numpy(raw.copy()).view(torch.bfloat16).float().numpy()
+        for b in range(B):
+            t0, Lpad = int(tok_off[b]), int(tok_off[b + 1] - tok_off[b])
+            for h in range(H):
+                base = (t0 * H + h * Lpad) * 128          # in bf16 elements: 256 bytes per key
+                blocks = vals[base: base + Lpad * 128].reshape(Lpad // 32, 4096)
+                # K chunk (s, lane), element e:  K[32kb + lane%32][16s + 8(lane/32) + e]
+                kf = blocks[:, :2048].reshape(-1, 4, 2, 32, 8)          # [kb][s][lane/32][lane%32][e]
+                K[l, t0:t0 + Lpad, h] = kf.transpose(0, 3, 1, 2, 4).reshape(Lpad, 64)
+                # V chunk (g, db, lane), element e:
+                #   V[32kb + 16g + 8(e/4) + 4(lane/32) + e%4][32db + lane%32]
+                vf = blocks[:, 2048:].reshape(-1, 2, 2, 2, 32, 2, 4)    # [kb][g][db][lane/32][lane%32][e/4][e%4]
+                V[l, t0:t0 + Lpad, h] = vf.transpose(0, 1, 5, 3, 6, 2, 4).reshape(Lpad, 64)
+    return K, V
+
+
 # ------------------------------------------------------------------ layer stack
-def stack_config(spec):
+def stack_config(spec, flags=0):
     import paper_2502_09888_amd as P
     return P.Config(n_layers=spec.n_layers, d_model=spec.d_model, n_heads=spec.H, d_head=spec.dh,
                     d_ffn=spec.d_ffn, n_scen=spec.n_scen, n_beh=spec.n_beh, sub_len=spec.sub_len,
-                    dtype=P.BF16, flags=P.HIST_CAUSAL if spec.causal else 0, qk_scale=spec.qk_scale,
-                    rms_eps=spec.rms_eps)
+                    dtype=P.BF16, flags=(P.HIST_CAUSAL if spec.causal else 0) | flags,
+                    qk_scale=spec.qk_scale, rms_eps=spec.rms_eps)
 
 
 def oracle_stack_config(spec):
@@ -155,12 +185,12 @@ def oracle_stack_config(spec):
 class GpuStack:
     """Device copies of one full-stack workload, cache and workspace."""
 
-    def __init__(self, w):
+    def __init__(self, w, flags=0):
         import torch
         import paper_2502_09888_amd as P
         self.P, self.torch, self.w = P, torch, w
         spec = w["spec"]
-        self.spec, self.cfg = spec, stack_config(spec)
+        self.spec, self.cfg = spec, stack_config(spec, flags)
         dev, bf = "cuda:0", torch.bfloat16
         self.layers = [{n.lower(): torch.from_numpy(lw[n]).to(dev).to(bf).contiguous()
                         for n in ("g1", "Wqkv", "Wo", "g2", "W1", "W2")} for lw in w["layers"]]

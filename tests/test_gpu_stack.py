@@ -8,13 +8,14 @@ import workloads as W
 from harness import GpuStack, max_abs, oracle_stack_users, say
 
 pytestmark = pytest.mark.gpu
+TWO_KERNEL, VIA_ROWS = 2, 4   # config flags: history pass route, keys / values through rows
 
 
-def run(spec, users):
+def run(spec, users, flags=0):
     say(f"[case] {spec.name} layers={spec.n_layers} d={spec.d_model} F={spec.d_ffn} B={spec.B} "
-        f"L={spec.L} sub={spec.sub_len} M={spec.M} seed={spec.seed}")
+        f"L={spec.L} sub={spec.sub_len} M={spec.M} flags={flags} seed={spec.seed}")
     w = W.make_stack(spec)
-    g = GpuStack(w)
+    g = GpuStack(w, flags=flags)
     g.encode()
     y = g.score()
     assert np.isfinite(y).all()
@@ -129,24 +130,69 @@ def test_prepacked_weights_give_the_same_bits():
     assert max_abs(y1, ref) < 2e-2
 
 
-def test_config4_full_size_sampled_users():
-    run(W.CONFIG4, users=(0, 31))
+def test_config4_full_size_every_user_and_cache():
+    # full size: every user's candidates against the oracle, and every layer of the cache, decoded
+    # from its operand-fragment layout, against the oracle's per-layer history keys / values
+    from harness import decode_bf16_cache, oracle_stack_config
+    import oracle
+    spec = W.CONFIG4
+    w, g, y = run(spec, users=tuple(range(spec.B)))
+    K, V = decode_bf16_cache(g.buf.cpu().numpy(), spec.B, w["tok_off"], spec.H, spec.n_layers)
+    kc, vc, _ = oracle.stack_encode(oracle_stack_config(spec), w["layers"], w["tau"], w["tok_off"],
+                                    w["hist_len"], w["x_hist"], w["scen"], w["beh"])
+    T = int(w["tok_off"][-1])
+    for l in range(spec.n_layers):
+        ek = max_abs(K[l].reshape(T, -1), kc[l])
+        ev = max_abs(V[l].reshape(T, -1), vc[l])
+        say(f"  layer {l}: cache K max-abs {ek:.3e}, V max-abs {ev:.3e} (|k| rms {np.sqrt((kc[l] ** 2).mean()):.3f})")
+        assert ek < 2e-2 and ev < 2e-2
+
+
+def test_small_stack_cache_contents_ragged():
+    # ragged batch: the decoded cache equals the oracle's keys / values on the valid rows of every
+    # layer and is zero in every padding slot, on both routes of the keys / values into the cache
+    from harness import decode_bf16_cache, oracle_stack_config
+    import oracle
+    spec = W.StackSpec("stack-cache-ragged", B=4, L=384, sub_len=128, M=0, n_layers=3, d_model=128, H=2,
+                       dh=64, d_ffn=256, n_scen=8, n_beh=4, seed=38, hist_lens=(384, 77, 300, 129),
+                       cand_counts=(9, 5, 0, 13), nan_padding=True)
+    w = W.make_stack(spec)
+    kc, vc, _ = oracle.stack_encode(oracle_stack_config(spec), w["layers"], w["tau"], w["tok_off"],
+                                    w["hist_len"], np.nan_to_num(w["x_hist"]), w["scen"], w["beh"])
+    T = int(w["tok_off"][-1])
+    ok = np.zeros(T, bool)
+    for b in range(spec.B):
+        ok[w["tok_off"][b]:w["tok_off"][b] + w["hist_len"][b]] = True
+    for flags in (0, VIA_ROWS):
+        say(f"[case] {spec.name} flags={flags}")
+        g = GpuStack(w, flags=flags)
+        g.buf.fill_(0x7f)
+        g.cache = g.P.climber_kv_cache_create(g.cfg, [int(x) for x in w["hist_len"]], g.padded, g.buf)
+        g.encode()
+        g.torch.cuda.synchronize()
+        K, V = decode_bf16_cache(g.buf.cpu().numpy(), spec.B, w["tok_off"], spec.H, spec.n_layers)
+        for l in range(spec.n_layers):
+            ek = max_abs(K[l].reshape(T, -1)[ok], kc[l][ok])
+            ev = max_abs(V[l].reshape(T, -1)[ok], vc[l][ok])
+            say(f"  layer {l}: cache K max-abs {ek:.3e}, V max-abs {ev:.3e}")
+            assert ek < 2e-2 and ev < 2e-2
+            assert np.all(K[l][~ok] == 0) and np.all(V[l][~ok] == 0)
 
 
 def test_projection_through_rows_path():
     # The fused projection writes keys and values straight into the cache; the same cases must hold
-    # when they go through rows and the cache writer (or the one-kernel history pass) instead, which
-    # the library reads from the environment once per process.
-    import os
-    import subprocess
-    import sys
-    if os.environ.get("CLIMBER_QKV_DIRECT") == "0":
-        pytest.skip("this is the child process")
-    env = dict(os.environ, CLIMBER_QKV_DIRECT="0")
-    here = os.path.dirname(os.path.abspath(__file__))
-    r = subprocess.run([sys.executable, "-u", "-m", "pytest", os.path.join(here, "test_gpu_stack.py"),
-                        "-m", "gpu", "-x", "-q", "-k", "all_users or uniform_partial or causal or ragged",
-                        "--timeout", "120", "--timeout-method", "thread"],
-                       env=env, capture_output=True, text=True, timeout=600)
-    say(r.stdout[-1500:])
-    assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-2000:]
+    # when they go through rows and the cache writer (or the one-kernel history pass) instead
+    for spec, users in (
+            (W.StackSpec("stack-small-rows", B=2, L=256, sub_len=128, M=70, n_layers=2, d_model=128, H=2,
+                         dh=64, d_ffn=256, n_scen=8, n_beh=4, seed=31), (0, 1)),
+            (W.StackSpec("stack-ragged-rows", B=4, L=384, sub_len=128, M=0, n_layers=3, d_model=128, H=2,
+                         dh=64, d_ffn=384, n_scen=8, n_beh=4, seed=33, hist_lens=(384, 77, 300, 129),
+                         cand_counts=(37, 5, 0, 130), nan_padding=True), (0, 1, 3)),
+            (W.StackSpec("stack-uniform-partial-rows", B=3, L=256, sub_len=128, M=45, n_layers=3,
+                         d_model=128, H=2, dh=64, d_ffn=256, n_scen=8, n_beh=4, seed=35,
+                         hist_lens=(203, 203, 203), nan_padding=True), (0, 2)),
+            (W.StackSpec("stack-causal-rows", B=2, L=256, sub_len=128, M=50, n_layers=3, d_model=128, H=2,
+                         dh=64, d_ffn=256, n_scen=8, n_beh=4, seed=34, hist_lens=(256, 200), causal=True,
+                         w_std=0.05), (0, 1))):
+        run(spec, users, flags=VIA_ROWS)
+        run(spec, users, flags=VIA_ROWS | TWO_KERNEL)

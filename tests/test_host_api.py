@@ -73,7 +73,7 @@ def test_create_rejects_bad_arguments():
     assert create(cfg(qk_scale=0.0), [64], [64]) == -5
     assert create(cfg(qk_scale=float("nan")), [64], [64]) == -5
     assert create(cfg(d_head=32), [64], [64]) == -7           # bf16 path needs d_head 64
-    assert create(cfg(flags=2), [64], [64]) == -2             # unknown flag bit
+    assert create(cfg(flags=8), [64], [64]) == -2             # unknown flag bit
     assert create(cfg(sub_len=96), [64], [64]) == -3
     assert create(cfg(d_model=100), [64], [64]) == -2
     assert create(cfg(n_scen=0), [64], [64]) == -2
@@ -96,6 +96,17 @@ def test_compute_calls_reject_missing_cache_and_pointers():
                                     None) == -1
     assert lib.climber_attn_sumi(None, FAKE, None, 0, FAKE, FAKE, FAKE, FAKE, 8, 8, FAKE, FAKE, FAKE,
                                  None) == -1
+
+
+def test_check_inputs_rejects_bad_arguments():
+    lib = P.load_library()
+    c = cfg()
+    f = lambda *a: lib.climber_check_inputs(*a)
+    assert f(C.byref(c), None, FAKE, FAKE, None, 8, FAKE, 2, 8, FAKE, None) == -1
+    assert f(C.byref(c), FAKE, FAKE, FAKE, None, 8, FAKE, 2, 8, None, None) == -1
+    assert f(C.byref(c), FAKE, FAKE, FAKE, None, -1, FAKE, 2, 8, FAKE, None) == -2
+    assert f(C.byref(c), FAKE, FAKE, FAKE, None, 8, FAKE, 0, 8, FAKE, None) == -2
+    assert f(None, FAKE, FAKE, FAKE, None, 8, FAKE, 2, 8, FAKE, None) == -1
 
 
 def test_workspace_bytes():

@@ -350,11 +350,12 @@ def test_layer_pieces_against_library_one_liners():
     assert np.abs(ge - F.gelu(torch.from_numpy(x)).numpy()).max() < 1e-14
 
 
-def tiny_stack(seed, n_layers=2, B=2, L=12, M=3, H=2, dh=4, F_=24, sub_len=4):
+def tiny_stack(seed, n_layers=2, B=2, L=12, M=3, H=2, dh=4, F_=24, sub_len=4, causal=False):
     spec = W.StackSpec("tiny", B=B, L=L, sub_len=sub_len, M=M, n_layers=n_layers, d_model=H * dh,
                        H=H, dh=dh, d_ffn=F_, n_scen=3, n_beh=2, w_std=0.3, pad_to=4, seed=seed)
     w = W.make_stack(spec)
-    cfg = oracle.StackConfig(n_layers, H * dh, H, dh, F_, 3, 2, sub_len=sub_len, qk_scale=0.5)
+    cfg = oracle.StackConfig(n_layers, H * dh, H, dh, F_, 3, 2, sub_len=sub_len, qk_scale=0.5,
+                             causal=causal)
     return spec, w, cfg
 
 
@@ -372,10 +373,13 @@ def torch_layer(cfg, lw, x, tau_row, vis):
     return y.numpy(), k.permute(1, 0, 2).reshape(-1, d).numpy(), v.permute(1, 0, 2).reshape(-1, d).numpy()
 
 
-def test_stack_cached_path_equals_bruteforce_and_library_composition():
+@pytest.mark.parametrize("causal", [False, True])
+def test_stack_cached_path_equals_bruteforce_and_library_composition(causal):
     # Sec. 3.2: encode once + score against cached K/V == every candidate appended alone to the
     # history and recomputed from scratch, all layers; cached K/V == the brute force's history K/V.
-    spec, w, cfg = tiny_stack(19)
+    # With the causal flag a history token sees the tokens j <= i of its subsequence only; the two
+    # variants must differ (else the flag would be pinned by nothing).
+    spec, w, cfg = tiny_stack(19, causal=causal)
     kc, vc, yh = oracle.stack_encode(cfg, w["layers"], w["tau"], w["tok_off"], w["hist_len"],
                                      w["x_hist"], w["scen"], w["beh"])
     y = oracle.stack_score(cfg, w["layers"], w["tau"], w["tok_off"], w["hist_len"], kc, vc,
@@ -393,6 +397,8 @@ def test_stack_cached_path_equals_bruteforce_and_library_composition():
             i = np.arange(L)
             vis = np.zeros((n, n), bool)
             vis[:L, :L] = (i[:, None] // S) == (i[None, :] // S)
+            if causal:
+                vis[:L, :L] &= i[None, :] <= i[:, None]
             vis[L] = True
             x = np.concatenate([w["x_hist"][t0:t0 + L], w["x_cand"][c:c + 1]]).astype(np.float64)
             for l in range(cfg.n_layers):
@@ -403,6 +409,11 @@ def test_stack_cached_path_equals_bruteforce_and_library_composition():
                 assert np.abs(v_l[:L] - vc[l, t0:t0 + L]).max() < 1e-12
             assert np.abs(x[L] - y[c]).max() < 1e-11
             assert np.abs(x[:L] - yh[t0:t0 + L]).max() < 1e-11
+    if causal:
+        _, w2, cfg2 = tiny_stack(19, causal=False)
+        kc2, _, yh2 = oracle.stack_encode(cfg2, w2["layers"], w2["tau"], w2["tok_off"], w2["hist_len"],
+                                          w2["x_hist"], w2["scen"], w2["beh"])
+        assert np.abs(yh2 - yh).max() > 1e-3 and np.abs(kc2[1] - kc[1]).max() > 1e-3
 
 
 def test_layer_masked_matches_library_composition():
