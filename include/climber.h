@@ -256,6 +256,27 @@ int climber_sumi_score(const climber_config *cfg, const climber_weights *weights
                        const int32_t *cand_beh, float *y_cand, void *workspace, size_t ws_bytes,
                        void *stream);
 
+/* climber_sumi_score for callers that cannot allocate or hand over device memory for scratch: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bitwise the same y_cand as climber_sumi_score, but the scratch lives in a fixed
+ * array of CLIMBER_STATIC_SCRATCH_BYTES inside the library (one per GPU, held until the process
+ * ends) instead of a caller's workspace, and the call allocates and frees nothing.
+ *  - weights->packed must be set (climber_pack_weights): CLIMBER_ERR_NULL otherwise.
+ *  - m_total is limited by the array: climber_workspace_bytes(cfg, m_total) minus
+ *    climber_packed_weights_bytes(cfg) must not exceed CLIMBER_STATIC_SCRATCH_BYTES
+ *    (2512 candidates at d_model 512, d_ffn 2048); beyond that CLIMBER_ERR_BUFSIZE and nothing is
+ *    launched.
+ *  - All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different
+ *    streams, different threads) race; serialise them.  The first call on a GPU looks the array's
+ *    address up (no allocation); make that call outside a graph capture.
+ * Other errors as climber_sumi_score. */
+#define CLIMBER_STATIC_SCRATCH_BYTES (32u << 20)
+int climber_sumi_score_static(const climber_config *cfg, const climber_weights *weights,
+                              const float *tau, const climber_kv_cache *cache, const void *x_cand,
+                              const int32_t *cand_off, int32_t m_total, int32_t m_max,
+                              const int32_t *cand_scen, const int32_t *cand_beh, float *y_cand,
+                              void *stream);
+
 #ifdef __cplusplus
 }
 #endif

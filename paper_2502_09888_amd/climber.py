@@ -92,6 +92,9 @@ def load_library():
     lib.climber_sumi_score.restype = C.c_int
     lib.climber_sumi_score.argtypes = [cfgp, C.POINTER(_Weights), vp, vp, vp, vp, i32, i32, vp,
                                        vp, vp, vp, sz, vp]
+    lib.climber_sumi_score_static.restype = C.c_int
+    lib.climber_sumi_score_static.argtypes = [cfgp, C.POINTER(_Weights), vp, vp, vp, vp, i32, i32, vp,
+                                              vp, vp, vp]
     _lib = lib
     return lib
 
@@ -250,3 +253,17 @@ def climber_sumi_score(cfg: Config, layers, tau, cache: KVCache, x_cand, cand_of
         C.byref(cfg), C.byref(w), _ptr(tau), cache.handle, _ptr(x_cand), _ptr(cand_off), m_total,
         m_max, _ptr(cand_scen), _ptr(cand_beh), _ptr(y_cand), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)), "climber_sumi_score")
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def climber_sumi_score_static(cfg: Config, layers, tau, cache: KVCache, x_cand, cand_off, m_total: int,
+                              m_max: int, cand_scen, cand_beh, y_cand, packed, stream=None) -> None:
+    """climber_sumi_score with the scratch in the library's fixed per-GPU array (allocates nothing)."""
+    w, keep = _weights_struct(layers if layers is not None else [], packed)
+    w.n_layers = cfg.n_layers
+    _ok(load_library().climber_sumi_score_static(
+        C.byref(cfg), C.byref(w), _ptr(tau), cache.handle, _ptr(x_cand), _ptr(cand_off), m_total,
+        m_max, _ptr(cand_scen), _ptr(cand_beh), _ptr(y_cand), _stream(stream)),
+        "climber_sumi_score_static")

@@ -11,6 +11,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include "gemm.h"
 
@@ -35,7 +36,7 @@ struct Workspace {
 
 struct PackedLayer { const uint8_t *wqkv, *wo, *w1, *w2; };
 
-Workspace carve(const climber_config *c, int64_t rows, void *base)
+Workspace carve(const climber_config *c, int64_t rows, void *base, bool with_weights = true)
 {
     const size_t d = c->d_model, F = c->d_ffn, n = (size_t)rows;
     uint8_t *p = (uint8_t *)base;
@@ -50,7 +51,7 @@ Workspace carve(const climber_config *c, int64_t rows, void *base)
     w.o = take(n * d * 2);
     w.u = take((n + 15) / 16 * 16 * F * 2);
     w.wlayer = up256((4 * d * d + 2 * d * F) * 2);
-    w.wpack = take(w.wlayer * (size_t)std::max(c->n_layers, 1));
+    w.wpack = with_weights ? take(w.wlayer * (size_t)std::max(c->n_layers, 1)) : nullptr;
     w.total = off;
     return w;
 }
@@ -193,6 +194,72 @@ int check_cand_args(const climber_config *cfg, const int32_t *cand_off, int32_t 
     return CLIMBER_OK;
 }
 
+int check_score_args(const climber_config *cfg, const climber_weights *weights, const float *tau,
+                     const climber_kv_cache *cache, const void *x_cand, const int32_t *cand_off,
+                     int32_t m_total, int32_t m_max, const int32_t *cand_scen, const int32_t *cand_beh,
+                     const float *y_cand)
+{
+    TRY(check_stack_config(cfg));
+    TRY(check_stack_call(cfg, cache, 0));
+    if (!tau || !x_cand || !cand_scen || !cand_beh || !y_cand) return CLIMBER_ERR_NULL;
+    TRY(check_weights(cfg, weights));
+    TRY(check_cand_args(cfg, cand_off, m_total, m_max));
+    if ((uintptr_t)x_cand % 16 != 0 || (uintptr_t)y_cand % 16 != 0) return CLIMBER_ERR_ALIGN;
+    return CLIMBER_OK;
+}
+
+// candidate rows through every layer against the cache; ws: carved scratch for m_total rows
+int score_layers(const climber_config *cfg, const climber_weights *weights, const float *tau,
+                 const climber_kv_cache *cache, const void *x_cand, const int32_t *cand_off,
+                 int32_t m_total, int32_t m_max, const int32_t *cand_scen, const int32_t *cand_beh,
+                 float *y_cand, Workspace &ws, hipStream_t s)
+{
+    if (m_total == 0) return CLIMBER_OK;
+    TRY(stage_weights(cfg, weights, ws, s));
+    TRY(rt(row_prep_bf16(x_cand, ws.x32, ws.ss, cfg->d_model / 64, m_total, cfg->d_model, s)));
+    const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const bool last = l + 1 == cfg->n_layers;
+        // the cache is only read in candidate mode
+        TRY(run_layer(cfg, packed_layer(cfg, ws, l), tau + l * tl, l, CLIMBER_MODE_CANDIDATE,
+                      const_cast<climber_kv_cache *>(cache), ws.x32, l == 0 ? x_cand : (const void *)ws.xb,
+                      last ? y_cand : ws.x32, !last, cand_scen, cand_beh, cand_off, m_total, m_max,
+                      m_total, ws, s));
+    }
+    return CLIMBER_OK;
+}
+
+// ---- scratch of the allocation-free scoring call ---------------------------------------------
+// One array per device, part of the library's code object: it exists on every GPU the library is
+// loaded on until the process ends.  Nothing in it has to start at zero (every region is written
+// before it is read within a call).  In host code the array's name is only a handle for the
+// symbol lookup; kernels are given the device address that lookup returned, one per device.
+static __device__ __align__(256) unsigned char scratch[CLIMBER_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+uint8_t *scratch_ptr[kMaxDevices];  // device address of `scratch` on device i, once looked up
+
+int static_scratch(uint8_t **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return CLIMBER_ERR_RUNTIME;
+    }
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return CLIMBER_ERR_RUNTIME;
+        }
+        scratch_ptr[dev] = (uint8_t *)ptr;
+    }
+    *out = scratch_ptr[dev];
+    return CLIMBER_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -290,29 +357,32 @@ int climber_sumi_score(const climber_config *cfg, const climber_weights *weights
                        const int32_t *cand_beh, float *y_cand, void *workspace, size_t ws_bytes,
                        void *stream)
 {
-    TRY(check_stack_config(cfg));
-    TRY(check_stack_call(cfg, cache, 0));
-    if (!tau || !x_cand || !cand_scen || !cand_beh || !y_cand || !workspace) return CLIMBER_ERR_NULL;
-    TRY(check_weights(cfg, weights));
-    TRY(check_cand_args(cfg, cand_off, m_total, m_max));
-    if ((uintptr_t)workspace % 256 != 0 || (uintptr_t)x_cand % 16 != 0 || (uintptr_t)y_cand % 16 != 0)
-        return CLIMBER_ERR_ALIGN;
+    TRY(check_score_args(cfg, weights, tau, cache, x_cand, cand_off, m_total, m_max, cand_scen, cand_beh,
+                         y_cand));
+    if (!workspace) return CLIMBER_ERR_NULL;
+    if ((uintptr_t)workspace % 256 != 0) return CLIMBER_ERR_ALIGN;
     Workspace ws = carve(cfg, m_total, workspace);
     if (ws_bytes < ws.total) return CLIMBER_ERR_BUFSIZE;
-    if (m_total == 0) return CLIMBER_OK;
-    hipStream_t s = (hipStream_t)stream;
-    TRY(stage_weights(cfg, weights, ws, s));
-    TRY(rt(row_prep_bf16(x_cand, ws.x32, ws.ss, cfg->d_model / 64, m_total, cfg->d_model, s)));
-    const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
-    for (int l = 0; l < cfg->n_layers; ++l) {
-        const bool last = l + 1 == cfg->n_layers;
-        // the cache is only read in candidate mode
-        TRY(run_layer(cfg, packed_layer(cfg, ws, l), tau + l * tl, l, CLIMBER_MODE_CANDIDATE,
-                      const_cast<climber_kv_cache *>(cache), ws.x32, l == 0 ? x_cand : (const void *)ws.xb,
-                      last ? y_cand : ws.x32, !last, cand_scen, cand_beh, cand_off, m_total, m_max,
-                      m_total, ws, s));
-    }
-    return CLIMBER_OK;
+    return score_layers(cfg, weights, tau, cache, x_cand, cand_off, m_total, m_max, cand_scen, cand_beh,
+                        y_cand, ws, (hipStream_t)stream);
+}
+
+int climber_sumi_score_static(const climber_config *cfg, const climber_weights *weights,
+                              const float *tau, const climber_kv_cache *cache, const void *x_cand,
+                              const int32_t *cand_off, int32_t m_total, int32_t m_max,
+                              const int32_t *cand_scen, const int32_t *cand_beh, float *y_cand,
+                              void *stream)
+{
+    TRY(check_score_args(cfg, weights, tau, cache, x_cand, cand_off, m_total, m_max, cand_scen, cand_beh,
+                         y_cand));
+    // the weights must come prepacked: packing them here would need room for them in the scratch array
+    if (!weights->packed) return CLIMBER_ERR_NULL;
+    if (carve(cfg, m_total, nullptr, false).total > CLIMBER_STATIC_SCRATCH_BYTES) return CLIMBER_ERR_BUFSIZE;
+    uint8_t *base = nullptr;
+    TRY(static_scratch(&base));
+    Workspace ws = carve(cfg, m_total, base, false);
+    return score_layers(cfg, weights, tau, cache, x_cand, cand_off, m_total, m_max, cand_scen, cand_beh,
+                        y_cand, ws, (hipStream_t)stream);
 }
 
 }  // extern "C"
