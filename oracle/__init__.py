@@ -127,6 +127,54 @@ def attn_sumi(tok_off, hist_len, cand_off, kh, vh, qc, kc, vc, cscen, cbeh, tau,
     return o
 
 
+def _bias_args(H, n_scen, n_beh, pos_table, time_table):
+    pt, tt = _f64(pos_table), _f64(time_table)
+    assert pt.shape[:3] == (n_scen, n_beh, H) and tt.shape[:3] == (n_scen, n_beh, H)
+    return pt, tt
+
+
+def attn_history_bias(tok_off, hist_len, q, k, v, scen, beh, tau, qk_scale, hist_pos, hist_ts,
+                      pos_table, time_table, sub_len=0, causal=False):
+    """attn_history with the relative attention bias of Eq. (3) added to the logits before the
+    temperature divide.  pos_table [n_scen, n_beh, H, n_pos] (n_pos odd), time_table
+    [n_scen, n_beh, H, n_time]; hist_pos, hist_ts: int32 [T_pad]."""
+    q, k, v, tau = _f64(q), _f64(k), _f64(v), _f64(tau)
+    tok_off, hist_len, scen, beh = _i32(tok_off), _i32(hist_len), _i32(scen), _i32(beh)
+    hist_pos, hist_ts = _i32(hist_pos), _i32(hist_ts)
+    T, H, dh = q.shape
+    B = len(hist_len)
+    pt, tt = _bias_args(H, tau.shape[0], tau.shape[1], pos_table, time_table)
+    assert tok_off[B] == T and hist_pos.shape == (T,) == hist_ts.shape
+    o = np.empty((T, H * dh))
+    _check(_load().oracle_attn_history_bias(B, _p(tok_off), _p(hist_len), H, dh, int(sub_len),
+                                            int(bool(causal)), _p(q), _p(k), _p(v), _p(scen), _p(beh),
+                                            _p(tau), tau.shape[0], tau.shape[1], C.c_double(qk_scale),
+                                            _p(hist_pos), _p(hist_ts), _p(pt), _p(tt), pt.shape[3],
+                                            tt.shape[3], _p(o)))
+    return o
+
+
+def attn_sumi_bias(tok_off, hist_len, cand_off, kh, vh, qc, kc, vc, cscen, cbeh, tau, qk_scale,
+                   hist_pos, hist_ts, cand_pos, cand_ts, pos_table, time_table):
+    """attn_sumi with the relative attention bias (a candidate's own key has zero distance)."""
+    kh, vh, qc, kc, vc, tau = _f64(kh), _f64(vh), _f64(qc), _f64(kc), _f64(vc), _f64(tau)
+    tok_off, hist_len, cand_off = _i32(tok_off), _i32(hist_len), _i32(cand_off)
+    cscen, cbeh = _i32(cscen), _i32(cbeh)
+    hist_pos, hist_ts, cand_pos, cand_ts = _i32(hist_pos), _i32(hist_ts), _i32(cand_pos), _i32(cand_ts)
+    T, H, dh = kh.shape
+    M = qc.shape[0]
+    B = len(hist_len)
+    pt, tt = _bias_args(H, tau.shape[0], tau.shape[1], pos_table, time_table)
+    assert tok_off[B] == T and cand_off[B] == M and cand_pos.shape == (M,) == cand_ts.shape
+    o = np.empty((M, H * dh))
+    _check(_load().oracle_attn_sumi_bias(B, _p(tok_off), _p(hist_len), _p(cand_off), H, dh, _p(kh),
+                                         _p(vh), _p(qc), _p(kc), _p(vc), _p(cscen), _p(cbeh), _p(tau),
+                                         tau.shape[0], tau.shape[1], C.c_double(qk_scale),
+                                         _p(hist_pos), _p(hist_ts), _p(cand_pos), _p(cand_ts), _p(pt),
+                                         _p(tt), pt.shape[3], tt.shape[3], _p(o)))
+    return o
+
+
 def rmsnorm(x, g, eps):
     x, g = _f64(x), _f64(g)
     n, d = x.shape

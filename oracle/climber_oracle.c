@@ -13,7 +13,8 @@
  *
  * What it follows (Climber, arXiv 2502.09888):
  *   - Adaptive Transformer Layer, Sec. 3.1.3, Eq. (3):
- *       R = Q K^T (+ bias, taken as 0 here), A = Softmax(R / f_tc), out = A V
+ *       R = Q K^T + f_b, A = Softmax(R / f_tc), out = A V
+ *     (f_b, the relative attention bias: the *_bias functions; 0 in the others)
  *     The equation carries no 1/sqrt(d_k); a caller-supplied qk_scale
  *     multiplies Q K^T so that both readings can be expressed.
  *   - the temperature f_tc is a positive scalar chosen per query row from a
@@ -41,7 +42,10 @@
  * Parity pins (see tests): library softmax attention at tau = 1, row-scaled
  * library attention for general tau, closed forms (tau -> inf mean, tau -> 0
  * arg-max, two-key hand formula), convexity, brute force of a candidate
- * appended alone to the history, numpy one-liners for the layer pieces.
+ * appended alone to the history, numpy one-liners for the layer pieces; for
+ * the bias term: zero tables reproduce the bias-free functions bit for bit, a
+ * constant bias changes nothing, library attention with an additive float
+ * mask, and a pure-Python loop with math.log2 / clipping on tiny inputs.
  * Model *quality* numbers of the paper (AUC tables) need its data and weights
  * and are not pinned: parity unpinned for those.
  */
@@ -271,6 +275,201 @@ int oracle_attn_sumi(int B, const int32_t *tok_off, const int32_t *hist_len,
                                   qk_scale, s, oc + (size_t)c * row + (size_t)h * dh, NULL);
                 }
                 free(keys); free(vals); free(s);
+            }
+        }
+    }
+    return rc;
+}
+
+/* ---- relative attention bias f_b (Eq. (3): R = Q K^T + f_b, divided by the temperature) ---- */
+/*
+ * Sec. 3.1.3 names the ingredients of the bias -- relative position and relative time, per
+ * extraction strategy and scenario -- but not its functional form.  The form fixed by this
+ * build (a reading, listed as such in the design notes):
+ *   bias(i, j; h) = P[g_i][h][bp(pos_i - pos_j)] + T[g_i][h][bt(ts_i - ts_j)]
+ *   g_i  = (scenario, behaviour) of the QUERY row i, the same pair that selects its temperature
+ *   bp(d) = clip(d, -half, half) + half,  half = (n_pos - 1) / 2        (n_pos odd)
+ *   bt(d) = min( floor(log2(max(|d|, 1))), n_time - 1 )
+ * pos / ts are integers given per history token and per candidate; a candidate's own key has
+ * d = 0 in both.  The bias is added to qk_scale <q,k> BEFORE the division by the temperature.
+ * Tables: P [n_scen][n_beh][H][n_pos], T [n_scen][n_beh][H][n_time], row-major doubles.
+ */
+static int bucket_pos(int64_t d, int n_pos)
+{
+    const int64_t half = (n_pos - 1) / 2;
+    if (d < -half) d = -half;
+    if (d > half) d = half;
+    return (int)(d + half);
+}
+
+static int bucket_time(int64_t d, int n_time)
+{
+    uint64_t a = (uint64_t)(d < 0 ? -d : d);
+    if (a < 1) a = 1;
+    int b = 0;
+    while (a > 1) { a >>= 1; ++b; }   /* floor(log2(a)) */
+    return b < n_time - 1 ? b : n_time - 1;
+}
+
+typedef struct {
+    const double *pos_table, *time_table;
+    int n_pos, n_time, H, n_beh;
+} bias_spec;
+
+static double bias_value(const bias_spec *bs, int scen, int beh, int h, int64_t dpos, int64_t dts)
+{
+    const size_t g = ((size_t)scen * bs->n_beh + beh) * bs->H + h;
+    return bs->pos_table[g * bs->n_pos + bucket_pos(dpos, bs->n_pos)] +
+           bs->time_table[g * bs->n_time + bucket_time(dts, bs->n_time)];
+}
+
+/* attention_row with an additive bias per visible key: r_j = qk_scale <q,k_j> + bias_j */
+static void attention_row_bias(int dh, const double *q, int n_vis, const double *const *keys,
+                               const double *const *vals, const double *bias, double tau,
+                               double qk_scale, double *scratch, double *o)
+{
+    double mx = -INFINITY;
+    for (int j = 0; j < n_vis; ++j) {
+        double dot = 0.0;
+        for (int e = 0; e < dh; ++e)
+            dot += q[e] * keys[j][e];
+        scratch[j] = (qk_scale * dot + bias[j]) / tau;
+        if (scratch[j] > mx)
+            mx = scratch[j];
+    }
+    double sum = 0.0;
+    for (int j = 0; j < n_vis; ++j) {
+        scratch[j] = exp(scratch[j] - mx);
+        sum += scratch[j];
+    }
+    for (int e = 0; e < dh; ++e)
+        o[e] = 0.0;
+    for (int j = 0; j < n_vis; ++j) {
+        double a = scratch[j] / sum;
+        for (int e = 0; e < dh; ++e)
+            o[e] += a * vals[j][e];
+    }
+}
+
+/* oracle_attn_history with the bias term; hist_pos, hist_ts: [T_pad] */
+int oracle_attn_history_bias(int B, const int32_t *tok_off, const int32_t *hist_len, int H, int dh,
+                             int sub_len, int causal, const double *q, const double *k,
+                             const double *v, const int32_t *scen, const int32_t *beh,
+                             const double *tau, int n_scen, int n_beh, double qk_scale,
+                             const int32_t *hist_pos, const int32_t *hist_ts,
+                             const double *pos_table, const double *time_table, int n_pos,
+                             int n_time, double *o)
+{
+    int rc = ORACLE_OK;
+    const size_t row = (size_t)H * dh;
+    if (n_pos < 1 || n_pos % 2 == 0 || n_time < 1)
+        return ORACLE_ERR_ID;
+    const bias_spec bs = {pos_table, time_table, n_pos, n_time, H, n_beh};
+    for (int b = 0; b < B; ++b) {
+        int Lp = tok_off[b + 1] - tok_off[b];
+        if (hist_len[b] < 0 || hist_len[b] > Lp)
+            return ORACLE_ERR_ID;
+        for (int i = hist_len[b]; i < Lp; ++i)
+            memset(o + (size_t)(tok_off[b] + i) * row, 0, sizeof(double) * row);
+    }
+    for (int b = 0; b < B; ++b) {
+        const int Lb = hist_len[b];
+        const size_t base = (size_t)tok_off[b];
+#pragma omp parallel for collapse(2) schedule(dynamic, 8)
+        for (int h = 0; h < H; ++h) {
+            for (int i = 0; i < Lb; ++i) {
+                double t;
+                int e = lookup_tau(tau, n_scen, n_beh, scen[base + i], beh[base + i], &t);
+                if (e) {
+#pragma omp atomic write
+                    rc = e;
+                    continue;
+                }
+                int lo = 0, hi = Lb;
+                if (sub_len > 0) {
+                    lo = (i / sub_len) * sub_len;
+                    hi = lo + sub_len < Lb ? lo + sub_len : Lb;
+                }
+                if (causal)
+                    hi = i + 1;
+                int nv = hi - lo;
+                const double **keys = malloc(sizeof(*keys) * (size_t)nv);
+                const double **vals = malloc(sizeof(*vals) * (size_t)nv);
+                double *s = malloc(sizeof(double) * (size_t)nv);
+                double *bj = malloc(sizeof(double) * (size_t)nv);
+                if (!keys || !vals || !s || !bj) {
+#pragma omp atomic write
+                    rc = ORACLE_ERR_ALLOC;
+                } else {
+                    for (int j = lo; j < hi; ++j) {
+                        keys[j - lo] = k + (base + j) * row + (size_t)h * dh;
+                        vals[j - lo] = v + (base + j) * row + (size_t)h * dh;
+                        bj[j - lo] = bias_value(&bs, scen[base + i], beh[base + i], h,
+                                                (int64_t)hist_pos[base + i] - hist_pos[base + j],
+                                                (int64_t)hist_ts[base + i] - hist_ts[base + j]);
+                    }
+                    attention_row_bias(dh, q + (base + i) * row + (size_t)h * dh, nv, keys, vals, bj,
+                                       t, qk_scale, s, o + (base + i) * row + (size_t)h * dh);
+                }
+                free(keys); free(vals); free(s); free(bj);
+            }
+        }
+    }
+    return rc;
+}
+
+/* oracle_attn_sumi with the bias term; cand_pos, cand_ts: [M_tot]; the own key has d = 0 */
+int oracle_attn_sumi_bias(int B, const int32_t *tok_off, const int32_t *hist_len,
+                          const int32_t *cand_off, int H, int dh, const double *kh,
+                          const double *vh, const double *qc, const double *kc, const double *vc,
+                          const int32_t *cscen, const int32_t *cbeh, const double *tau, int n_scen,
+                          int n_beh, double qk_scale, const int32_t *hist_pos,
+                          const int32_t *hist_ts, const int32_t *cand_pos, const int32_t *cand_ts,
+                          const double *pos_table, const double *time_table, int n_pos, int n_time,
+                          double *oc)
+{
+    int rc = ORACLE_OK;
+    const size_t row = (size_t)H * dh;
+    if (n_pos < 1 || n_pos % 2 == 0 || n_time < 1)
+        return ORACLE_ERR_ID;
+    const bias_spec bs = {pos_table, time_table, n_pos, n_time, H, n_beh};
+    for (int b = 0; b < B; ++b) {
+        const int Lb = hist_len[b];
+        const size_t base = (size_t)tok_off[b];
+        const int c0 = cand_off[b], c1 = cand_off[b + 1];
+#pragma omp parallel for collapse(2) schedule(dynamic, 8)
+        for (int h = 0; h < H; ++h) {
+            for (int c = c0; c < c1; ++c) {
+                double t;
+                int e = lookup_tau(tau, n_scen, n_beh, cscen[c], cbeh[c], &t);
+                if (e) {
+#pragma omp atomic write
+                    rc = e;
+                    continue;
+                }
+                int nv = Lb + 1;
+                const double **keys = malloc(sizeof(*keys) * (size_t)nv);
+                const double **vals = malloc(sizeof(*vals) * (size_t)nv);
+                double *s = malloc(sizeof(double) * (size_t)nv);
+                double *bj = malloc(sizeof(double) * (size_t)nv);
+                if (!keys || !vals || !s || !bj) {
+#pragma omp atomic write
+                    rc = ORACLE_ERR_ALLOC;
+                } else {
+                    for (int j = 0; j < Lb; ++j) {
+                        keys[j] = kh + (base + j) * row + (size_t)h * dh;
+                        vals[j] = vh + (base + j) * row + (size_t)h * dh;
+                        bj[j] = bias_value(&bs, cscen[c], cbeh[c], h,
+                                           (int64_t)cand_pos[c] - hist_pos[base + j],
+                                           (int64_t)cand_ts[c] - hist_ts[base + j]);
+                    }
+                    keys[Lb] = kc + (size_t)c * row + (size_t)h * dh;
+                    vals[Lb] = vc + (size_t)c * row + (size_t)h * dh;
+                    bj[Lb] = bias_value(&bs, cscen[c], cbeh[c], h, 0, 0);
+                    attention_row_bias(dh, qc + (size_t)c * row + (size_t)h * dh, nv, keys, vals, bj,
+                                       t, qk_scale, s, oc + (size_t)c * row + (size_t)h * dh);
+                }
+                free(keys); free(vals); free(s); free(bj);
             }
         }
     }

@@ -445,3 +445,138 @@ def test_config1_oracle_against_library():
     # unit-scale check of the recipe: logits have roughly unit variance
     logits = np.einsum("chd,jhd->chj", w["qc"].astype(np.float64), w["kh"].astype(np.float64))
     assert 0.7 < logits.std() < 1.4
+
+
+# ------------------------------------------------ relative attention bias (Eq. (3): R = QK^T + f_b)
+def bias_case(seed, **kw):
+    base = dict(name="bias-tiny", B=2, L=40, L_min=9, sub_len=16, M=6, M_min=2, H=2, dh=8, n_scen=3, n_beh=2,
+                pad_to=4, seed=seed, qk_scale=0.3, dtype="f32", std=1.0)
+    base.update(kw)
+    spec = W.AttnSpec(**base)
+    return spec, W.add_bias_inputs(W.make_attention(spec), n_pos=9, n_time=6)
+
+
+def hist_bias(spec, w, causal=False, **over):
+    a = dict(w, **over)
+    return oracle.attn_history_bias(a["tok_off"], a["hist_len"], a["qh"], a["kh"], a["vh"], a["scen"], a["beh"],
+                                    a["tau"], spec.qk_scale, a["hist_pos"], a["hist_ts"], a["pos_table"],
+                                    a["time_table"], sub_len=spec.sub_len, causal=causal)
+
+
+def sumi_bias(spec, w, **over):
+    a = dict(w, **over)
+    return oracle.attn_sumi_bias(a["tok_off"], a["hist_len"], a["cand_off"], a["kh"], a["vh"], a["qc"], a["kc"],
+                                 a["vc"], a["cscen"], a["cbeh"], a["tau"], spec.qk_scale, a["hist_pos"],
+                                 a["hist_ts"], a["cand_pos"], a["cand_ts"], a["pos_table"], a["time_table"])
+
+
+def test_bias_zero_tables_reproduce_the_bias_free_functions_bitwise():
+    spec, w = bias_case(71)
+    z = dict(pos_table=np.zeros_like(w["pos_table"]), time_table=np.zeros_like(w["time_table"]))
+    for causal in (False, True):
+        ref = oracle.attn_history(w["tok_off"], w["hist_len"], w["qh"], w["kh"], w["vh"], w["scen"], w["beh"],
+                                  w["tau"], spec.qk_scale, sub_len=spec.sub_len, causal=causal)
+        assert np.array_equal(hist_bias(spec, w, causal=causal, **z), ref)
+    ref = oracle.attn_sumi(w["tok_off"], w["hist_len"], w["cand_off"], w["kh"], w["vh"], w["qc"], w["kc"],
+                           w["vc"], w["cscen"], w["cbeh"], w["tau"], spec.qk_scale)
+    assert np.array_equal(sumi_bias(spec, w, **z), ref)
+    # and the tables of the case do change the result (else the pins below would pin nothing)
+    assert np.abs(sumi_bias(spec, w) - ref).max() > 1e-2
+
+
+def test_bias_constant_along_a_row_changes_nothing():
+    # a bias that does not depend on the key (tables constant over their buckets, but different per
+    # (scenario, behaviour, head)) shifts every logit of a row alike: softmax is unchanged
+    spec, w = bias_case(72)
+    g = rng(720)
+    cp = g.standard_normal(w["pos_table"].shape[:3])[..., None] * np.ones(w["pos_table"].shape[3])
+    ct = g.standard_normal(w["time_table"].shape[:3])[..., None] * np.ones(w["time_table"].shape[3])
+    z = dict(pos_table=np.zeros_like(cp), time_table=np.zeros_like(ct))
+    c = dict(pos_table=cp, time_table=ct)
+    assert np.abs(hist_bias(spec, w, **c) - hist_bias(spec, w, **z)).max() < 1e-12
+    assert np.abs(sumi_bias(spec, w, **c) - sumi_bias(spec, w, **z)).max() < 1e-12
+
+
+def np_bias_matrix(w, b, h, scen_q, beh_q, pos_q, ts_q, pos_k, ts_k):
+    """bias[i, j] from numpy clipping / log2 (an implementation of its own of the bucket rules)."""
+    n_pos, n_time = w["pos_table"].shape[3], w["time_table"].shape[3]
+    half = (n_pos - 1) // 2
+    dp = np.clip(pos_q[:, None].astype(np.int64) - pos_k[None, :], -half, half) + half
+    dt = np.abs(ts_q[:, None].astype(np.int64) - ts_k[None, :])
+    bt = np.minimum(np.floor(np.log2(np.maximum(dt, 1))).astype(np.int64), n_time - 1)
+    P = w["pos_table"].astype(np.float64)[scen_q, beh_q, h]      # [nq, n_pos]
+    Tt = w["time_table"].astype(np.float64)[scen_q, beh_q, h]
+    return np.take_along_axis(P, dp, 1) + np.take_along_axis(Tt, bt, 1)
+
+
+def test_bias_is_library_attention_with_an_additive_mask():
+    # (qk_scale QK^T + bias) / tau == SDPA on queries divided by tau with the float mask bias / tau
+    spec, w = bias_case(73)
+    got_h, got_c = hist_bias(spec, w), sumi_bias(spec, w)
+    tq = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    for b in range(spec.B):
+        t0, Lb = int(w["tok_off"][b]), int(w["hist_len"][b])
+        c0, c1 = int(w["cand_off"][b]), int(w["cand_off"][b + 1])
+        sl = slice(t0, t0 + Lb)
+        tau_h = w["tau"].astype(np.float64)[w["scen"][sl], w["beh"][sl]]
+        i = np.arange(Lb)
+        vis = (i[:, None] // spec.sub_len) == (i[None, :] // spec.sub_len)
+        for h in range(spec.H):
+            bm = np_bias_matrix(w, b, h, w["scen"][sl], w["beh"][sl], w["hist_pos"][sl], w["hist_ts"][sl],
+                                w["hist_pos"][sl], w["hist_ts"][sl])
+            mask = np.where(vis, bm / tau_h[:, None], -np.inf)
+            ref = F.scaled_dot_product_attention(tq(w["qh"][sl, h] / tau_h[:, None])[None], tq(w["kh"][sl, h])[None],
+                                                 tq(w["vh"][sl, h])[None], attn_mask=tq(mask)[None],
+                                                 scale=spec.qk_scale)[0].numpy()
+            assert np.abs(got_h[sl, h * spec.dh:(h + 1) * spec.dh] - ref).max() < 1e-12
+            for c in range(c0, c1):
+                tau_c = float(w["tau"][w["cscen"][c], w["cbeh"][c]])
+                pk = np.concatenate([w["hist_pos"][sl], w["cand_pos"][c:c + 1]])
+                tk = np.concatenate([w["hist_ts"][sl], w["cand_ts"][c:c + 1]])
+                bm = np_bias_matrix(w, b, h, w["cscen"][c:c + 1], w["cbeh"][c:c + 1], w["cand_pos"][c:c + 1],
+                                    w["cand_ts"][c:c + 1], pk, tk)
+                kk = np.concatenate([w["kh"][sl, h], w["kc"][c:c + 1, h]])
+                vv = np.concatenate([w["vh"][sl, h], w["vc"][c:c + 1, h]])
+                ref = F.scaled_dot_product_attention(tq(w["qc"][c:c + 1, h].astype(np.float64) / tau_c)[None], tq(kk)[None], tq(vv)[None],
+                                                     attn_mask=tq(bm / tau_c)[None], scale=spec.qk_scale)[0].numpy()
+                assert np.abs(got_c[c, h * spec.dh:(h + 1) * spec.dh] - ref[0]).max() < 1e-12
+
+
+def test_bias_brute_force_python_loops_and_bucket_edges():
+    # the definition written out with math only, on a tiny case whose distances hit both clip ends of
+    # the position buckets and the open-ended last time bucket
+    spec, w = bias_case(74, B=1, L=12, L_min=12, sub_len=0, M=2, M_min=2, H=1, dh=4)
+    w["hist_ts"][:12] = np.array([5, 5, 6, 8, 9, 13, 40, 41, 300, 301, 70000, 2_000_000_000], np.int32)
+    w["cand_ts"][:] = np.array([2_000_000_000, 2_000_000_100], np.int32)
+    n_pos, n_time = 9, 6
+    P, Tt = w["pos_table"].astype(np.float64), w["time_table"].astype(np.float64)
+
+    def bias(sc, bh, dp, dt):
+        bp = max(-4, min(4, dp)) + 4
+        a = max(abs(dt), 1)
+        bt = min(int(math.floor(math.log2(a))), n_time - 1)
+        return P[sc, bh, 0, bp] + Tt[sc, bh, 0, bt]
+
+    def attend(q, keys, vals, biases, tau):
+        r = [(spec.qk_scale * sum(float(a) * float(b) for a, b in zip(q, k)) + bb) / tau for k, bb in zip(keys, biases)]
+        m = max(r)
+        e = [math.exp(x - m) for x in r]
+        z = sum(e)
+        return [sum(e[j] / z * float(vals[j][d]) for j in range(len(keys))) for d in range(len(q))]
+
+    got_h = hist_bias(spec, w, causal=True)
+    for i in range(12):
+        sc, bh = int(w["scen"][i]), int(w["beh"][i])
+        js = range(i + 1)
+        ref = attend(w["qh"][i, 0], [w["kh"][j, 0] for j in js], [w["vh"][j, 0] for j in js],
+                     [bias(sc, bh, i - j, int(w["hist_ts"][i]) - int(w["hist_ts"][j])) for j in js],
+                     float(w["tau"][sc, bh]))
+        assert np.abs(got_h[i] - np.array(ref)).max() < 1e-12
+    got_c = sumi_bias(spec, w)
+    for c in range(2):
+        sc, bh = int(w["cscen"][c]), int(w["cbeh"][c])
+        keys = [w["kh"][j, 0] for j in range(12)] + [w["kc"][c, 0]]
+        vals = [w["vh"][j, 0] for j in range(12)] + [w["vc"][c, 0]]
+        bs = [bias(sc, bh, 12 - j, int(w["cand_ts"][c]) - int(w["hist_ts"][j])) for j in range(12)] + [bias(sc, bh, 0, 0)]
+        ref = attend(w["qc"][c, 0], keys, vals, bs, float(w["tau"][sc, bh]))
+        assert np.abs(got_c[c] - np.array(ref)).max() < 1e-12

@@ -184,3 +184,37 @@ def make_stack(spec: StackSpec) -> dict:
         for b in range(spec.B):
             w["x_hist"][tok_off[b] + hist_len[b]:tok_off[b + 1]] = np.nan
     return w
+
+
+def add_bias_inputs(w: dict, n_pos: int = 33, n_time: int = 12, table_std: float = 0.5,
+                    seed: int = 7) -> dict:
+    """Inputs of the relative attention bias for an attention workload (random draws only):
+    positions = index of the token in its user's history, candidates at the position after the
+    history; timestamps = increasing, with gaps spread over five decades (the log-scale time
+    buckets all occur), candidates a little after the user's last behaviour; bias tables
+    N(0, table_std^2) per (scenario, behaviour, head, bucket), stored as float32."""
+    spec = w["spec"]
+    rng = _rng(spec.seed * 1000 + seed)
+    T, Mt = int(w["tok_off"][-1]), int(w["cand_off"][-1])
+    hist_pos = np.zeros(T, np.int32)
+    hist_ts = np.zeros(T, np.int32)
+    cand_pos = np.zeros(Mt, np.int32)
+    cand_ts = np.zeros(Mt, np.int32)
+    for b in range(spec.B):
+        t0, t1 = int(w["tok_off"][b]), int(w["tok_off"][b + 1])
+        n = t1 - t0
+        hist_pos[t0:t1] = np.arange(n)
+        gaps = np.exp2(rng.uniform(0.0, 17.0, size=n)).astype(np.int64)
+        ts = 1_000_000 + np.cumsum(gaps)
+        hist_ts[t0:t1] = np.minimum(ts, 2_000_000_000).astype(np.int32)
+        c0, c1 = int(w["cand_off"][b]), int(w["cand_off"][b + 1])
+        Lb = int(w["hist_len"][b])
+        cand_pos[c0:c1] = Lb
+        last = int(hist_ts[t0 + Lb - 1]) if Lb > 0 else 1_000_000
+        cand_ts[c0:c1] = last + rng.integers(0, 5000, size=c1 - c0)
+    H = spec.H
+    w = dict(w)
+    w.update(hist_pos=hist_pos, hist_ts=hist_ts, cand_pos=cand_pos, cand_ts=cand_ts,
+             pos_table=(rng.standard_normal((spec.n_scen, spec.n_beh, H, n_pos)) * table_std).astype(np.float32),
+             time_table=(rng.standard_normal((spec.n_scen, spec.n_beh, H, n_time)) * table_std).astype(np.float32))
+    return w
