@@ -182,6 +182,42 @@ int climber_attn_sumi(const climber_config *cfg, const float *tau_layer,
                       int32_t m_max, const int32_t *cand_scen, const int32_t *cand_beh, void *o_c,
                       void *stream);
 
+/* ---- relative attention bias (Eq. (3): R = Q K^T + f_b, divided by the temperature) -----------
+ * Sec. 3.1.3 names what the bias depends on (relative position and relative time, per extraction
+ * strategy and scenario) and not its form.  The form of this library:
+ *     bias(i, j; h) = pos_table[scen_i][beh_i][h][bp(pos_i - pos_j)]
+ *                   + time_table[scen_i][beh_i][h][bt(ts_i - ts_j)]
+ *     bp(d) = clip(d, -(n_pos-1)/2, (n_pos-1)/2) + (n_pos-1)/2          (n_pos odd, >= 1)
+ *     bt(d) = min( floor(log2(max(|d|, 1))), n_time - 1 )               (n_time >= 1)
+ * i = query row (its scenario / behaviour ids select the table row, as they select its temperature),
+ * j = key; pos / ts are caller-defined integers per history row and per candidate (e.g. index in the
+ * history and seconds); a candidate's own key has distance 0 in both.  The bias is added to
+ * qk_scale <q_i, k_j> and the sum is divided by the row's temperature.
+ * All pointers dev; tables fp32 (both precision paths); hist_pos / hist_ts: int32 [rows], 16-byte
+ * aligned, padded rows may hold anything; cand_pos / cand_ts: int32 [m_total]. */
+typedef struct climber_rel_bias {
+    const float *pos_table;  /* [n_scen][n_beh][n_heads][n_pos] */
+    const float *time_table; /* [n_scen][n_beh][n_heads][n_time] */
+    int32_t n_pos, n_time;
+    const int32_t *hist_pos, *hist_ts;
+    const int32_t *cand_pos, *cand_ts; /* only read by climber_attn_sumi_bias */
+} climber_rel_bias;
+
+/* climber_attn_history / climber_attn_sumi with the bias term (bias != NULL; everything else as
+ * documented there).  The bf16 history pass takes the cache writer + tiled attention route.
+ * Additional errors: CLIMBER_ERR_NULL (bias or a pointer it needs), _SHAPE (n_pos even or < 1,
+ * n_time < 1), _ALIGN (hist_pos / hist_ts). */
+int climber_attn_history_bias(const climber_config *cfg, const float *tau_layer, const void *q,
+                              const void *k, const void *v, const int32_t *scen, const int32_t *beh,
+                              climber_kv_cache *cache, int32_t layer, void *o_hist,
+                              const climber_rel_bias *bias, void *stream);
+int climber_attn_sumi_bias(const climber_config *cfg, const float *tau_layer,
+                           const climber_kv_cache *cache, int32_t layer, const void *q_c,
+                           const void *k_c, const void *v_c, const int32_t *cand_off,
+                           int32_t m_total, int32_t m_max, const int32_t *cand_scen,
+                           const int32_t *cand_beh, void *o_c, const climber_rel_bias *bias,
+                           void *stream);
+
 /* ---- debug check of device-resident inputs -----------------------------------------------------
  * Eq. (3) divides a row's logits by tau[scen][beh]: the ids must lie inside the table and the entry
  * must be finite and > 0.  Ids, offsets and the table live in device memory, so the compute calls

@@ -38,6 +38,13 @@ class LayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("g1", "wqkv", "wo", "g2", "w1", "w2")]
 
 
+class RelBias(C.Structure):
+    """Mirror of ``climber_rel_bias`` (device pointers).  Build with ``rel_bias(...)``."""
+    _fields_ = [("pos_table", C.c_void_p), ("time_table", C.c_void_p), ("n_pos", C.c_int32),
+                ("n_time", C.c_int32), ("hist_pos", C.c_void_p), ("hist_ts", C.c_void_p),
+                ("cand_pos", C.c_void_p), ("cand_ts", C.c_void_p)]
+
+
 class _Weights(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(LayerWeights)), ("packed", C.c_void_p)]
 
@@ -75,6 +82,11 @@ def load_library():
     lib.climber_attn_history.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.climber_attn_sumi.restype = C.c_int
     lib.climber_attn_sumi.argtypes = [cfgp, vp, vp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.climber_attn_history_bias.restype = C.c_int
+    lib.climber_attn_history_bias.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, vp, C.POINTER(RelBias), vp]
+    lib.climber_attn_sumi_bias.restype = C.c_int
+    lib.climber_attn_sumi_bias.argtypes = [cfgp, vp, vp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp,
+                                           C.POINTER(RelBias), vp]
     lib.climber_check_inputs.restype = C.c_int
     lib.climber_check_inputs.argtypes = [cfgp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp]
     lib.climber_workspace_bytes.restype = sz
@@ -267,3 +279,27 @@ def climber_sumi_score_static(cfg: Config, layers, tau, cache: KVCache, x_cand, 
         C.byref(cfg), C.byref(w), _ptr(tau), cache.handle, _ptr(x_cand), _ptr(cand_off), m_total,
         m_max, _ptr(cand_scen), _ptr(cand_beh), _ptr(y_cand), _stream(stream)),
         "climber_sumi_score_static")
+
+
+def rel_bias(pos_table, time_table, hist_pos, hist_ts, cand_pos=None, cand_ts=None) -> RelBias:
+    """climber_rel_bias from device tensors: tables [n_scen, n_beh, H, n_pos] / [..., n_time] fp32."""
+    rb = RelBias(_ptr(pos_table), _ptr(time_table), int(pos_table.shape[-1]), int(time_table.shape[-1]),
+                 _ptr(hist_pos), _ptr(hist_ts), _ptr(cand_pos), _ptr(cand_ts))
+    rb._keep = (pos_table, time_table, hist_pos, hist_ts, cand_pos, cand_ts)
+    return rb
+
+
+def climber_attn_history_bias(cfg: Config, tau_layer, q, k, v, scen, beh, cache: KVCache, layer: int,
+                              o_hist, bias: RelBias, stream=None) -> None:
+    _ok(load_library().climber_attn_history_bias(C.byref(cfg), _ptr(tau_layer), _ptr(q), _ptr(k), _ptr(v),
+                                                 _ptr(scen), _ptr(beh), cache.handle, layer, _ptr(o_hist),
+                                                 C.byref(bias), _stream(stream)), "climber_attn_history_bias")
+
+
+def climber_attn_sumi_bias(cfg: Config, tau_layer, cache: KVCache, layer: int, q_c, k_c, v_c, cand_off,
+                           m_total: int, m_max: int, cand_scen, cand_beh, o_c, bias: RelBias,
+                           stream=None) -> None:
+    _ok(load_library().climber_attn_sumi_bias(C.byref(cfg), _ptr(tau_layer), cache.handle, layer, _ptr(q_c),
+                                              _ptr(k_c), _ptr(v_c), _ptr(cand_off), m_total, m_max,
+                                              _ptr(cand_scen), _ptr(cand_beh), _ptr(o_c), C.byref(bias),
+                                              _stream(stream)), "climber_attn_sumi_bias")

@@ -55,7 +55,9 @@ struct KParams {
     int B, H, n_scen, n_beh, sub_len, n_qtiles;
     int uni_len, uni_pad;  // >= 0: every user has this valid / padded history length
     int uni_cand;          // >= 0: every user has this many candidates (SUMI)
-    float scale_log2e;
+    float scale_log2e, inv_qk_scale;
+    BiasArgs bias;  // relative attention bias (the BIAS variants of the kernel)
+    int bias_H;
 };
 
 // wait until at most `tiles_in_flight` later tiles (NPRE loads each) are still outstanding
@@ -76,7 +78,12 @@ __device__ __forceinline__ void wait_tiles(int tiles_in_flight)
     }
 }
 
-template <int NW, int QB, bool SUMI, bool CAUSAL = false>
+// BIAS: the relative attention bias of Eq. (3) joins the logits before the temperature divide.  A
+// lane works its 16 bias values of a block out of the two bucket tables (clipped relative position,
+// log2 bucket of the time distance; one table row per (scenario, behaviour, head) of the query) and
+// hands them to the S^T MFMAs as the initial value of the accumulator, scaled like the logits
+// (FAST: by log2(e)/tau, SAFE: by 1/qk_scale, the fp32 scale of the pass doing the rest).
+template <int NW, int QB, bool SUMI, bool CAUSAL = false, bool BIAS = false>
 __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 {
     static_assert(!(SUMI && CAUSAL), "the causal flag concerns the history pass");
@@ -174,6 +181,31 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     };
     auto issue_tile = [&](int t) __attribute__((always_inline)) { issue_tile_at(t, (t % kStages) * kTileBytes); };
     QState<QB> st;
+    // per query row of the lane: position, time stamp, rows of the two bias tables, logit scale
+    int b_pos[QB], b_ts[QB], b_prow[QB], b_trow[QB];
+    float fb[QB], bias_self[QB];
+    auto qk = [&](const KFrags &kf, f32x16 (&S)[QB], int blk_lo) __attribute__((always_inline)) {
+        if constexpr (BIAS) {
+            const int half = (p.bias.n_pos - 1) >> 1;
+            const int64_t kr = (int64_t)t0 + blk_lo + 4 * hf;  // packed history row of the lane's first key
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int4 kp = *(const int4 *)(p.bias.key_pos + kr + 8 * g4);
+                const int4 kt = *(const int4 *)(p.bias.key_ts + kr + 8 * g4);
+                const int kpe[4] = {kp.x, kp.y, kp.z, kp.w}, kte[4] = {kt.x, kt.y, kt.z, kt.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb)
+                        S[qb][4 * g4 + e] =
+                            fb[qb] * (p.bias.pos_table[b_prow[qb] + bias_bucket_pos(b_pos[qb], kpe[e], half)] +
+                                      p.bias.time_table[b_trow[qb] + bias_bucket_time(b_ts[qb], kte[e], p.bias.n_time)]);
+            }
+            qk_block_acc(st, kf, S);
+        } else {
+            qk_block(st, kf, S);
+        }
+    };
 
     // FAST start: q' = bf16(q*c) from the raw rows in st.qf, empty state (the candidate's own
     // key/value joins later, from the landing buffer).
@@ -222,7 +254,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             // maximum the reference (0 would leave rows whose logits are all very negative with an
             // empty sum).  Every row sees a key of its first block, so the reference is finite
             // before the first exponential.
-            st.m_ref[qb] = SUMI ? dot + xhalf(dot) : kSafeNoRef;
+            if constexpr (BIAS) fb[qb] = p.inv_qk_scale;  // SAFE: logits in raw units, scaled by c in fp32
+            st.m_ref[qb] = SUMI ? dot + xhalf(dot) + (BIAS ? fb[qb] * bias_self[qb] : 0.f) : kSafeNoRef;
             st.l[qb] = (SUMI && hfs == 0) ? 1.f : 0.f;
             if (SUMI) {
                 const __bf16 *vp = p.v_self + row * p.ld_kv + h * kDHead + 4 * hfs;
@@ -300,7 +333,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) dot += (float)qq[e] * (float)kk[e];
             }
-            w_own[qb] = __builtin_amdgcn_exp2f(dot + xhalf(dot));
+            w_own[qb] = __builtin_amdgcn_exp2f(dot + xhalf(dot) + (BIAS ? fb[qb] * bias_self[qb] : 0.f));
             st.l[qb] += hf == 0 ? w_own[qb] : 0.f;
         }
     };
@@ -342,6 +375,15 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         const int sc = min(max(tau_idx[qb], 0), p.n_scen - 1);
         const int bhv = min(max(beh_id[qb], 0), p.n_beh - 1);
         tau_idx[qb] = sc * p.n_beh + bhv;
+        if constexpr (BIAS) {
+            const int64_t row = row0 + min(wave * WQ + qb * 32 + l32, nq - 1);
+            b_pos[qb] = p.bias.q_pos[row];
+            b_ts[qb] = p.bias.q_ts[row];
+            b_prow[qb] = (tau_idx[qb] * p.bias_H + h) * p.bias.n_pos;
+            b_trow[qb] = (tau_idx[qb] * p.bias_H + h) * p.bias.n_time;
+            // a candidate's own key: zero distance in position and time
+            bias_self[qb] = p.bias.pos_table[b_prow[qb] + ((p.bias.n_pos - 1) >> 1)] + p.bias.time_table[b_trow[qb]];
+        }
     }
     // tile 0 and the query rows of this wave have landed (only tile 1 may still be in flight);
     // tau_lds is visible to the workgroup after the bare barrier (a fence would also wait for
@@ -357,6 +399,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
             c[qb] = p.scale_log2e / (tau_in_lds ? tau_lds[tau_idx[qb]] : p.tau[tau_idx[qb]]);
+        if constexpr (BIAS) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) fb[qb] = c[qb] * p.inv_qk_scale;  // log2(e) / tau
+        }
         load_q_lds();
         init_fast(c);
     }
@@ -369,7 +415,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         __builtin_amdgcn_s_barrier();
         {
             const KFrags k0 = load_k(lds, lane);
-            qk_block(st, k0, S0);
+            qk(k0, S0, k_lo);
             causal(S0, k_lo);
         }
         // One step = every tile but the last: 64 unmasked keys.  EV numbers the tile that becomes
@@ -388,7 +434,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 const KFrags k1 = load_k(cur + kBlockBytes, lane);
                 const VFrags v0 = load_v(cur, lane);
                 __builtin_amdgcn_sched_barrier(0);
-                qk_block(st, k1, S1);
+                qk(k1, S1, k_lo + t * kTileKeys + kBlockKeys);
                 causal(S1, k_lo + t * kTileKeys + kBlockKeys);
                 softmax_fast(st, S0, P);
                 pv_block(st, v0, P);
@@ -408,7 +454,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 const KFrags k0 = load_k(nxt, lane);
                 const VFrags v1 = load_v(cur + kBlockBytes, lane);
                 __builtin_amdgcn_sched_barrier(0);
-                qk_block(st, k0, S0);
+                qk(k0, S0, k_lo + (t + 1) * kTileKeys);
                 causal(S0, k_lo + (t + 1) * kTileKeys);
                 softmax_fast(st, S1, P);
                 pv_block(st, v1, P);
@@ -441,7 +487,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             const bool two = tile_lo + kBlockKeys < k_hi;
             if (two) {
                 const KFrags k1 = load_k(cur + kBlockBytes, lane);
-                qk_block(st, k1, S1);
+                qk(k1, S1, tile_lo + kBlockKeys);
                 causal(S1, tile_lo + kBlockKeys);
             }
             if (tile_lo + kBlockKeys > k_hi) mask_block(S0, hf, tile_lo, k_hi);
@@ -513,7 +559,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                     f32x16 S[QB];
                     bf16x8 P[QB][2];
                     const KFrags kf = load_k(cur + blk * kBlockBytes, lane);
-                    qk_block(st, kf, S);
+                    qk(kf, S, blk_lo);
                     if (blk_lo + kBlockKeys > k_hi) mask_block(S, hf, blk_lo, k_hi);
                     causal(S, blk_lo);
                     softmax_safe(st, S, P);
@@ -585,13 +631,16 @@ KParams make_params(const AttnArgs &a, int n_qtiles)
     p.sub_len = a.sub_len;
     p.n_qtiles = n_qtiles;
     p.scale_log2e = a.qk_scale * 1.4426950408889634f;
+    p.inv_qk_scale = 1.f / a.qk_scale;
+    p.bias = a.bias;
+    p.bias_H = a.H;
     p.uni_len = a.uni_len;
     p.uni_pad = a.uni_pad;
     p.uni_cand = a.uni_cand;
     return p;
 }
 
-template <int NW, int QB, bool SUMI, bool CAUSAL = false>
+template <int NW, int QB, bool SUMI, bool CAUSAL = false, bool BIAS = false>
 hipError_t launch(const AttnArgs &a, hipStream_t s)
 {
     constexpr int TQ = NW * 32 * QB;
@@ -600,7 +649,7 @@ hipError_t launch(const AttnArgs &a, hipStream_t s)
     const int64_t grid = (int64_t)8 * n_qtiles * groups;
     if (grid <= 0 || grid > 0x7fffffff) return hipErrorInvalidValue;
     const KParams p = make_params(a, n_qtiles);
-    hipLaunchKernelGGL((attn_bf16_kernel<NW, QB, SUMI, CAUSAL>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<NW, QB, SUMI, CAUSAL, BIAS>), dim3((unsigned)grid), dim3(NW * 64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -611,12 +660,14 @@ hipError_t launch(const AttnArgs &a, hipStream_t s)
 
 hipError_t launch_attn_sumi_bf16(const AttnArgs &a, hipStream_t s)
 {
+    if (a.bias.pos_table) return launch<4, 1, true, false, true>(a, s);
     return a.max_rows_per_user > 128 ? launch<4, 2, true>(a, s) : launch<4, 1, true>(a, s);
 }
 
 hipError_t launch_attn_hist_bf16(const AttnArgs &a, hipStream_t s)
 {
     // a query tile must lie inside one subsequence (sub_len is 0 or a multiple of 128)
+    if (a.bias.pos_table) return a.causal ? launch<4, 1, false, true, true>(a, s) : launch<4, 1, false, false, true>(a, s);
     const bool wide = a.sub_len % 256 == 0;
     if (a.causal) return wide ? launch<4, 2, false, true>(a, s) : launch<4, 1, false, true>(a, s);
     return wide ? launch<4, 2, false>(a, s) : launch<4, 1, false>(a, s);

@@ -82,6 +82,17 @@ static __device__ __forceinline__ void qk_block(const QState<QB> &st, const KFra
             S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k.a[s], st.qf[qb][s], S[qb], 0, 0, 0);
 }
 
+// S^T[qb] += K_blk q_qb^T onto whatever S holds (the relative attention bias of the block)
+template <int QB>
+static __device__ __forceinline__ void qk_block_acc(const QState<QB> &st, const KFrags &k, f32x16 (&S)[QB])
+{
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+            S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k.a[s], st.qf[qb][s], S[qb], 0, 0, 0);
+}
+
 // O^T[db][qb] += V^T_{g,db} P^T
 template <int QB>
 static __device__ __forceinline__ void pv_block(QState<QB> &st, const VFrags &v, const bf16x8 (&P)[QB][2])

@@ -62,12 +62,24 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnArgs a, int64_t total_
     const int bv = min(max(a.beh[row], 0), a.n_beh - 1);
     const float tau = a.tau[sc * a.n_beh + bv];
 
+    const bool bias_on = a.bias.pos_table != nullptr;
+    const int q_pos = bias_on ? a.bias.q_pos[row] : 0, q_ts = bias_on ? a.bias.q_ts[row] : 0;
+    const int64_t grp = ((int64_t)sc * a.n_beh + bv) * a.H + h;
+    const int64_t prow = grp * a.bias.n_pos, trow = grp * a.bias.n_time;
+
     float mx = -INFINITY;
     for (int j = lane; j < nk; j += 64) {
         const float *kp = j < nh ? kc + ((int64_t)(t0 + lo + j) * a.H + h) * dh : ks;
         float dot = 0.f;
         for (int e = 0; e < dh; ++e) dot = fmaf(q[e], kp[e], dot);
-        const float s = a.qk_scale * dot / tau;
+        float s = a.qk_scale * dot;
+        if (bias_on) {  // Eq. (3): the bias joins the logit before the temperature divide
+            const int kp_ = j < nh ? a.bias.key_pos[t0 + lo + j] : q_pos;
+            const int kt_ = j < nh ? a.bias.key_ts[t0 + lo + j] : q_ts;
+            s += a.bias.pos_table[prow + bias_bucket_pos(q_pos, kp_, (a.bias.n_pos - 1) >> 1)] +
+                 a.bias.time_table[trow + bias_bucket_time(q_ts, kt_, a.bias.n_time)];
+        }
+        s /= tau;
         logit[j] = s;
         mx = fmaxf(mx, s);
     }

@@ -129,12 +129,12 @@ namespace climber {
 int attn_history_strided(const climber_config *cfg, const float *tau_layer, const void *q,
                          const void *k, const void *v, int64_t ld, const int32_t *scen,
                          const int32_t *beh, climber_kv_cache *cache, int32_t layer, void *o,
-                         int64_t ld_o, hipStream_t s)
+                         int64_t ld_o, hipStream_t s, const climber_rel_bias *bias)
 {
     const CacheView cv = view_of(cache, layer);
     if (cache->rows == 0) return CLIMBER_OK;
     // short subsequences, bf16: one kernel writes the cache and attends (K/V rows read once)
-    const bool fused = cfg->dtype == CLIMBER_BF16 && o && !(cfg->flags & CLIMBER_HIST_TWO_KERNEL) &&
+    const bool fused = cfg->dtype == CLIMBER_BF16 && o && !bias && !(cfg->flags & CLIMBER_HIST_TWO_KERNEL) &&
                        hist_fused_supported(cfg->sub_len, (cfg->flags & CLIMBER_HIST_CAUSAL) != 0);
     if (fused) {
     } else if (cfg->dtype == CLIMBER_BF16) {
@@ -157,6 +157,8 @@ int attn_history_strided(const climber_config *cfg, const float *tau_layer, cons
     a.ld_o = ld_o;
     a.max_rows_per_user = cache->max_pad;
     a.total_q_rows = cache->rows;
+    if (bias) a.bias = BiasArgs{bias->pos_table, bias->time_table, bias->hist_pos, bias->hist_ts, bias->hist_pos,
+                                bias->hist_ts, bias->n_pos, bias->n_time};
     if (fused) return rt(launch_hist_fused_bf16(a, s));
     if (cfg->dtype == CLIMBER_BF16) return rt(launch_attn_hist_bf16(a, s));
     return rt(launch_attn_f32(a, false, cache->rows, s));
@@ -204,7 +206,7 @@ int attn_sumi_strided(const climber_config *cfg, const float *tau_layer,
                       const climber_kv_cache *cache, int32_t layer, const void *q, const void *k,
                       const void *v, int64_t ld, const int32_t *cand_off, int32_t m_total,
                       int32_t m_max, const int32_t *cscen, const int32_t *cbeh, void *o,
-                      int64_t ld_o, hipStream_t s)
+                      int64_t ld_o, hipStream_t s, const climber_rel_bias *bias)
 {
     if (m_total == 0) return CLIMBER_OK;
     AttnArgs a = base_args(cfg, cache, layer, tau_layer);
@@ -222,6 +224,8 @@ int attn_sumi_strided(const climber_config *cfg, const float *tau_layer,
     a.total_q_rows = m_total;
     // m_max >= every user's count and the counts sum to m_total: equality means all are m_max
     if ((int64_t)m_max * cache->B == (int64_t)m_total) a.uni_cand = m_max;
+    if (bias) a.bias = BiasArgs{bias->pos_table, bias->time_table, bias->hist_pos, bias->hist_ts, bias->cand_pos,
+                                bias->cand_ts, bias->n_pos, bias->n_time};
     if (cfg->dtype == CLIMBER_BF16) return rt(launch_attn_sumi_bf16(a, s));
     return rt(launch_attn_f32(a, true, cache->rows, s));
 }
@@ -339,9 +343,19 @@ int64_t climber_kv_cache_rows(const climber_kv_cache *cache)
     return cache ? cache->rows : (int64_t)CLIMBER_ERR_NULL;
 }
 
-int climber_attn_history(const climber_config *cfg, const float *tau_layer, const void *q,
-                         const void *k, const void *v, const int32_t *scen, const int32_t *beh,
-                         climber_kv_cache *cache, int32_t layer, void *o_hist, void *stream)
+static int check_bias(const climber_rel_bias *b, bool sumi)
+{
+    if (!b || !b->pos_table || !b->time_table || !b->hist_pos || !b->hist_ts) return CLIMBER_ERR_NULL;
+    if (sumi && (!b->cand_pos || !b->cand_ts)) return CLIMBER_ERR_NULL;
+    if (b->n_pos < 1 || b->n_pos % 2 == 0 || b->n_time < 1) return CLIMBER_ERR_SHAPE;
+    if (!aligned(b->hist_pos, 16) || !aligned(b->hist_ts, 16)) return CLIMBER_ERR_ALIGN;
+    return CLIMBER_OK;
+}
+
+static int attn_history_call(const climber_config *cfg, const float *tau_layer, const void *q,
+                             const void *k, const void *v, const int32_t *scen, const int32_t *beh,
+                             climber_kv_cache *cache, int32_t layer, void *o_hist,
+                             const climber_rel_bias *bias, void *stream)
 {
     int e = check_config(cfg);
     if (e) return e;
@@ -352,14 +366,31 @@ int climber_attn_history(const climber_config *cfg, const float *tau_layer, cons
     if (!aligned(k, 16) || !aligned(v, 16) || !aligned(q, 16) || !aligned(o_hist, 16))
         return CLIMBER_ERR_ALIGN;
     return attn_history_strided(cfg, tau_layer, q, k, v, cfg->d_model, scen, beh, cache, layer,
-                                o_hist, cfg->d_model, (hipStream_t)stream);
+                                o_hist, cfg->d_model, (hipStream_t)stream, bias);
 }
 
-int climber_attn_sumi(const climber_config *cfg, const float *tau_layer,
-                      const climber_kv_cache *cache, int32_t layer, const void *q_c,
-                      const void *k_c, const void *v_c, const int32_t *cand_off, int32_t m_total,
-                      int32_t m_max, const int32_t *cand_scen, const int32_t *cand_beh, void *o_c,
-                      void *stream)
+int climber_attn_history(const climber_config *cfg, const float *tau_layer, const void *q,
+                         const void *k, const void *v, const int32_t *scen, const int32_t *beh,
+                         climber_kv_cache *cache, int32_t layer, void *o_hist, void *stream)
+{
+    return attn_history_call(cfg, tau_layer, q, k, v, scen, beh, cache, layer, o_hist, nullptr, stream);
+}
+
+int climber_attn_history_bias(const climber_config *cfg, const float *tau_layer, const void *q,
+                              const void *k, const void *v, const int32_t *scen, const int32_t *beh,
+                              climber_kv_cache *cache, int32_t layer, void *o_hist,
+                              const climber_rel_bias *bias, void *stream)
+{
+    const int e = check_bias(bias, false);
+    if (e) return e;
+    return attn_history_call(cfg, tau_layer, q, k, v, scen, beh, cache, layer, o_hist, bias, stream);
+}
+
+static int attn_sumi_call(const climber_config *cfg, const float *tau_layer,
+                          const climber_kv_cache *cache, int32_t layer, const void *q_c,
+                          const void *k_c, const void *v_c, const int32_t *cand_off, int32_t m_total,
+                          int32_t m_max, const int32_t *cand_scen, const int32_t *cand_beh, void *o_c,
+                          const climber_rel_bias *bias, void *stream)
 {
     int e = check_config(cfg);
     if (e) return e;
@@ -374,7 +405,30 @@ int climber_attn_sumi(const climber_config *cfg, const float *tau_layer,
         return CLIMBER_ERR_ALIGN;
     return attn_sumi_strided(cfg, tau_layer, cache, layer, q_c, k_c, v_c, cfg->d_model, cand_off,
                              m_total, m_max, cand_scen, cand_beh, o_c, cfg->d_model,
-                             (hipStream_t)stream);
+                             (hipStream_t)stream, bias);
+}
+
+int climber_attn_sumi(const climber_config *cfg, const float *tau_layer,
+                      const climber_kv_cache *cache, int32_t layer, const void *q_c,
+                      const void *k_c, const void *v_c, const int32_t *cand_off, int32_t m_total,
+                      int32_t m_max, const int32_t *cand_scen, const int32_t *cand_beh, void *o_c,
+                      void *stream)
+{
+    return attn_sumi_call(cfg, tau_layer, cache, layer, q_c, k_c, v_c, cand_off, m_total, m_max, cand_scen,
+                          cand_beh, o_c, nullptr, stream);
+}
+
+int climber_attn_sumi_bias(const climber_config *cfg, const float *tau_layer,
+                           const climber_kv_cache *cache, int32_t layer, const void *q_c,
+                           const void *k_c, const void *v_c, const int32_t *cand_off,
+                           int32_t m_total, int32_t m_max, const int32_t *cand_scen,
+                           const int32_t *cand_beh, void *o_c, const climber_rel_bias *bias,
+                           void *stream)
+{
+    const int e = check_bias(bias, true);
+    if (e) return e;
+    return attn_sumi_call(cfg, tau_layer, cache, layer, q_c, k_c, v_c, cand_off, m_total, m_max, cand_scen,
+                          cand_beh, o_c, bias, stream);
 }
 
 int climber_check_inputs(const climber_config *cfg, const float *tau_layer, const int32_t *scen,

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "bias.h"
+
 namespace climber {
 
 // ---- bf16 KV-cache geometry (d_head = 64) ---------------------------------------------------
@@ -45,6 +47,7 @@ struct AttnArgs {
     int uni_len, uni_pad;            // >= 0: all users share this valid / padded history length
     int uni_cand;                    // >= 0: all users have this many candidates (SUMI)
     float qk_scale;
+    BiasArgs bias;                   // relative attention bias; bias.pos_table == nullptr: none
 };
 
 // bf16 MFMA flash attention (attn_bf16.hip)

@@ -12,12 +12,12 @@ namespace climber {
 int attn_history_strided(const climber_config *cfg, const float *tau_layer, const void *q,
                          const void *k, const void *v, int64_t ld, const int32_t *scen,
                          const int32_t *beh, climber_kv_cache *cache, int32_t layer, void *o,
-                         int64_t ld_o, hipStream_t s);
+                         int64_t ld_o, hipStream_t s, const climber_rel_bias *bias = nullptr);
 int attn_sumi_strided(const climber_config *cfg, const float *tau_layer,
                       const climber_kv_cache *cache, int32_t layer, const void *q, const void *k,
                       const void *v, int64_t ld, const int32_t *cand_off, int32_t m_total,
                       int32_t m_max, const int32_t *cscen, const int32_t *cbeh, void *o,
-                      int64_t ld_o, hipStream_t s);
+                      int64_t ld_o, hipStream_t s, const climber_rel_bias *bias = nullptr);
 // History attention over a cache layer whose keys and values are already in place (written by the
 // fused projection's epilogue, see QkvToCache in gemm.h): bf16 path only.
 int attn_history_cached(const climber_config *cfg, const float *tau_layer, const void *q, int64_t ld_q,

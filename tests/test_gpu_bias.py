@@ -1,0 +1,144 @@
+"""GPU parity of the relative attention bias (Eq. (3): R = Q K^T + f_b, divided by the temperature):
+the bias entry points of the C ABI against the oracle's *_bias functions on the same seeded inputs.
+Bucket decisions are integer arithmetic on both sides, so they agree exactly; tolerances as for the
+bias-free attention (1e-4 fp32, 2e-2 bf16)."""
+import numpy as np
+import pytest
+
+import workloads as W
+from harness import GpuAttention, max_abs, oracle, say, valid_rows
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+class GpuBias(GpuAttention):
+    def __init__(self, w, causal=False):
+        super().__init__(w, causal=causal)
+        t = self.torch
+        dev = "cuda:0"
+        for n in ("hist_pos", "hist_ts", "cand_pos", "cand_ts", "pos_table", "time_table"):
+            setattr(self, n, t.from_numpy(w[n]).to(dev).contiguous())
+        self.rb = self.P.rel_bias(self.pos_table, self.time_table, self.hist_pos, self.hist_ts, self.cand_pos,
+                                  self.cand_ts)
+
+    def history_bias(self):
+        t = self.torch
+        o = t.full((self.qh.shape[0], self.d), float("nan"), dtype=self.dt, device="cuda:0")
+        self.P.climber_attn_history_bias(self.cfg, self.tau, self.qh, self.kh, self.vh, self.scen, self.beh,
+                                         self.cache, 0, o, self.rb)
+        t.cuda.synchronize()
+        return o.float().cpu().numpy()
+
+    def sumi_bias(self):
+        t, w = self.torch, self.w
+        m_total = int(w["cand_off"][-1])
+        m_max = int(np.diff(w["cand_off"]).max()) if m_total else 0
+        o = t.full((max(m_total, 1), self.d), float("nan"), dtype=self.dt, device="cuda:0")
+        self.P.climber_attn_sumi_bias(self.cfg, self.tau, self.cache, 0, self.qc, self.kc, self.vc, self.cand_off,
+                                      m_total, m_max, self.cscen, self.cbeh, o, self.rb)
+        t.cuda.synchronize()
+        return o[:m_total].float().cpu().numpy()
+
+
+def oracle_hist_bias(w, causal=False):
+    s = w["spec"]
+    return oracle.attn_history_bias(w["tok_off"], w["hist_len"], w["qh"], w["kh"], w["vh"], w["scen"], w["beh"],
+                                    w["tau"], s.qk_scale, w["hist_pos"], w["hist_ts"], w["pos_table"],
+                                    w["time_table"], sub_len=s.sub_len, causal=causal)
+
+
+def oracle_sumi_bias(w):
+    s = w["spec"]
+    return oracle.attn_sumi_bias(w["tok_off"], w["hist_len"], w["cand_off"], w["kh"], w["vh"], w["qc"], w["kc"],
+                                 w["vc"], w["cscen"], w["cbeh"], w["tau"], s.qk_scale, w["hist_pos"], w["hist_ts"],
+                                 w["cand_pos"], w["cand_ts"], w["pos_table"], w["time_table"])
+
+
+def check_bias(w, causal=False):
+    spec = w["spec"]
+    say(f"[case] bias {spec.name} dtype={spec.dtype} B={spec.B} L={spec.L} sub={spec.sub_len} M={spec.M} H={spec.H} "
+        f"qk_scale={spec.qk_scale} causal={causal} n_pos={w['pos_table'].shape[3]} n_time={w['time_table'].shape[3]}")
+    g = GpuBias(w, causal=causal)
+    tol = TOL[spec.dtype]
+    oh = g.history_bias()
+    ok = valid_rows(w)
+    e = max_abs(oh[ok], oracle_hist_bias(w, causal=causal)[ok])
+    say(f"  history+bias max-abs {e:.3e}")
+    assert np.isfinite(oh[ok]).all() and e < tol and np.all(oh[~ok] == 0)
+    os_ = g.sumi_bias()
+    ref = oracle_sumi_bias(w)
+    e = max_abs(os_, ref)
+    # the bias must matter in the case: without it the result is far from the reference
+    plain = g.sumi()
+    say(f"  sumi+bias max-abs {e:.3e} (bias-free kernel output differs from it by {max_abs(plain, ref):.2e})")
+    assert np.isfinite(os_).all() and e < tol
+    assert max_abs(plain, ref) > 5 * tol
+    return g, os_
+
+
+def test_fp32_bias_both_masks_ragged():
+    spec = W.shrink(W.CONFIG1, name="f32-bias", B=3, L=90, L_min=10, M=11, M_min=1, sub_len=32, pad_to=8,
+                    nan_padding=True, dh=48, H=3, seed=81)
+    w = W.add_bias_inputs(W.make_attention(spec), n_pos=15, n_time=9)
+    check_bias(w)
+    check_bias(w, causal=True)
+    check_bias(W.add_bias_inputs(W.make_attention(W.CONFIG1)))
+
+
+def test_bf16_bias_multi_tile_ragged_both_masks():
+    spec = W.shrink(W.CONFIG5, name="bf16-bias-ragged", B=4, L=700, L_min=1, sub_len=256, M=200, M_min=1, H=2,
+                    seed=82)
+    w = W.add_bias_inputs(W.make_attention(spec))
+    check_bias(w)
+    check_bias(w, causal=True)
+    spec = W.shrink(W.CONFIG2, name="bf16-bias-onesub", B=2, L=333, L_min=77, sub_len=0, M=70, H=1,
+                    nan_padding=True, seed=83)
+    check_bias(W.add_bias_inputs(W.make_attention(spec), n_pos=5, n_time=3))
+
+
+def test_bf16_bias_single_bucket_tables_and_edges():
+    # n_pos = n_time = 1: one entry per (scenario, behaviour, head), i.e. a constant along every row,
+    # which softmax ignores: the result equals the bias-free one; and timestamps at the int32 ends
+    spec = W.shrink(W.CONFIG2, name="bf16-bias-const", B=2, L=256, sub_len=128, M=60, H=2, seed=84)
+    w = W.add_bias_inputs(W.make_attention(spec), n_pos=1, n_time=1, table_std=3.0)
+    w["hist_ts"][::7] = -2_000_000_000
+    w["cand_ts"][::5] = 2_000_000_000
+    g = GpuBias(w)
+    g.history(want_output=False)
+    ref = oracle_sumi_bias(w)
+    e = max_abs(g.sumi_bias(), ref)
+    say(f"[case] bias {spec.name}: sumi+bias max-abs {e:.3e}; vs bias-free oracle "
+        f"{max_abs(ref, oracle.attn_sumi(w['tok_off'], w['hist_len'], w['cand_off'], w['kh'], w['vh'], w['qc'], w['kc'], w['vc'], w['cscen'], w['cbeh'], w['tau'], spec.qk_scale)):.1e}")
+    assert e < 2e-2
+
+
+def test_bf16_bias_large_logits_take_the_running_maximum_pass():
+    spec = W.shrink(W.CONFIG2, name="bf16-bias-biglogits", B=2, L=256, sub_len=128, M=100, H=2, qk_scale=12.0,
+                    seed=85)
+    check_bias(W.add_bias_inputs(W.make_attention(spec), table_std=20.0))
+
+
+def test_bf16_bias_zero_tables_equal_the_bias_free_kernel_bitwise():
+    spec = W.shrink(W.CONFIG2, name="bf16-bias-zero", B=2, L=384, sub_len=128, M=100, H=2, seed=86)
+    w = W.add_bias_inputs(W.make_attention(spec))
+    w["pos_table"][:] = 0
+    w["time_table"][:] = 0
+    g = GpuBias(w)
+    g.history(want_output=False)
+    assert np.array_equal(g.sumi_bias(), g.sumi())
+
+
+def test_bias_at_config2_and_config3_shapes():
+    for spec in (W.CONFIG2, W.CONFIG3):
+        w = W.add_bias_inputs(W.make_attention(spec))
+        say(f"[case] bias {spec.name} full size")
+        g = GpuBias(w)
+        oh = g.history_bias()
+        ok = valid_rows(w)
+        e = max_abs(oh[ok], oracle_hist_bias(w)[ok])
+        say(f"  history+bias max-abs {e:.3e}")
+        assert e < 2e-2
+        e = max_abs(g.sumi_bias(), oracle_sumi_bias(w))
+        say(f"  sumi+bias max-abs over all users {e:.3e}")
+        assert e < 2e-2
