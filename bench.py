@@ -317,6 +317,51 @@ def main():
     score_with(other)
     other_ms = timed(lambda: score_with(other), args.steps)
 
+    # the 4 x 128 scoring of configuration 3 as written, with the four calls on four streams of equal
+    # (default) priority: the cache is immutable while scoring, so the calls may overlap; the chunks of
+    # one head then run at the same time and share its K/V in L2 instead of re-reading it from HBM
+    ch4 = other if other_n == 4 else chunks
+    side = [torch.cuda.Stream() for _ in range(4)]
+    fork, join = torch.cuda.Event(), [torch.cuda.Event() for _ in range(4)]
+
+    def score_4_streams():
+        main = torch.cuda.current_stream()
+        fork.record(main)
+        for st_, ch, ev_ in zip(side, ch4, join):
+            st_.wait_event(fork)
+            P.climber_attn_sumi(cfg, tau, cache, 0, ch["q"], ch["k"], ch["v"], ch["off"], B * ch["mc"], ch["mc"],
+                                ch["s"], ch["b"], ch["o"], stream=st_)
+            ev_.record(st_)
+        for ev_ in join:
+            main.wait_event(ev_)
+
+    score_4_streams()
+    torch.cuda.synchronize()
+    streams_ms = timed(score_4_streams, args.steps)
+    flop_all = 4.0 * (L + 1) * dh * H * B * M
+
+    # relative attention bias (Eq. (3)): the same launches with the bias term, for their cost
+    wb = W.add_bias_inputs(w)
+    bt = {n: torch.from_numpy(wb[n]).to(dev).contiguous() for n in ("hist_pos", "hist_ts", "cand_pos", "cand_ts",
+                                                                     "pos_table", "time_table")}
+    rb = P.rel_bias(bt["pos_table"], bt["time_table"], bt["hist_pos"], bt["hist_ts"], bt["cand_pos"], bt["cand_ts"])
+    o_b = torch.empty((B * M, d), dtype=bf, device=dev)
+    off_all = torch.arange(B + 1, device=dev, dtype=torch.int32) * M
+
+    def sumi_bias():
+        P.climber_attn_sumi_bias(cfg, tau, cache, 0, t_["qc"], t_["kc"], t_["vc"], off_all, B * M, M, ids["cscen"],
+                                 ids["cbeh"], o_b, rb)
+
+    def hist_bias():
+        P.climber_attn_history_bias(cfg, tau, t_["qh"], t_["kh"], t_["vh"], ids["scen"], ids["beh"], cache, 0,
+                                    s0.o_hist, rb)
+
+    sumi_bias()
+    hist_bias()
+    torch.cuda.synchronize()
+    sumi_bias_ms, hist_bias_ms = timed(sumi_bias, 20), timed(hist_bias, 20)
+    encode()   # the cache as the bias-free history call leaves it (the bias calls wrote the same K/V)
+
     # what was timed, for the parity figure of the cpu_baseline leg: every user's outputs
     score()
     torch.cuda.synchronize()
@@ -357,6 +402,21 @@ def main():
                                         "mfma_frac_per_launch": 4.0 * (L + 1) * dh * H * B * M / (other_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}},
         "parity_max_abs_vs_oracle": None,   # filled by the cpu_baseline leg (the only user of the oracle)
     }
+    single_ms = sumi_ms if nch == 1 else other_ms
+    seq4_ms = other_ms if nch == 1 else sumi_ms * 4
+    # configuration 3 scores its 512 candidates per user "in 4 chunks of 128": both forms side by side
+    # (scoring launches only; frac = algorithmic flop of all 512 candidates / time / bf16 MFMA peak)
+    out["variants"] = {
+        "one_call_of_512": {"score_ms": single_ms, "candidates_per_s": cands / (single_ms * 1e-3),
+                            "mfma_frac": flop_all / (single_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "four_calls_of_128_one_stream": {"score_ms": seq4_ms, "candidates_per_s": cands / (seq4_ms * 1e-3),
+                                         "mfma_frac": flop_all / (seq4_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "four_calls_of_128_four_streams": {"score_ms": streams_ms, "candidates_per_s": cands / (streams_ms * 1e-3),
+                                           "mfma_frac": flop_all / (streams_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}}
+    out["breakdown"]["relative_attention_bias"] = {
+        "sumi_with_bias_ms": sumi_bias_ms, "sumi_without_ms": score_ms if nch == 1 else other_ms,
+        "history_with_bias_ms": hist_bias_ms, "history_without_ms": encode_ms,
+        "sumi_with_bias_mfma_frac": flop_all / (sumi_bias_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
 
     if not args.no_naive:
         # "single user, single item": the history is re-encoded for every candidate.  Timed on a

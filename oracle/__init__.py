@@ -309,3 +309,20 @@ def stack_score(cfg: StackConfig, layers, tau, tok_off, hist_len, k_cache, v_cac
                                       _p(k_cache), _p(v_cache), _p(cand_off), _p(x_cand),
                                       _p(cscen), _p(cbeh), _p(y)))
     return y
+
+
+def stack_packed(cfg: StackConfig, layers, tau, x_hist, scen, beh, x_cand, cscen, cbeh):
+    """Training-side "single user, multiple items" forward of ONE user (Sec. 3.2): the valid history
+    rows and all candidates as one packed sequence under the mask of that section, no cache.
+    Returns (y_hist [L, d], y_cand [M, d])."""
+    w, keep = _weights(cfg, layers)
+    tau, x_hist, x_cand = _f64(tau), _f64(x_hist), _f64(x_cand)
+    scen, beh, cscen, cbeh = _i32(scen), _i32(beh), _i32(cscen), _i32(cbeh)
+    L, d = x_hist.shape
+    M = x_cand.shape[0]
+    assert tau.shape == (cfg.n_layers, cfg.n_scen, cfg.n_beh) and x_cand.shape == (M, d)
+    yh, yc = np.empty((L, d)), np.empty((M, d))
+    cc = cfg._c()
+    _check(_load().oracle_stack_packed(C.byref(cc), w, _p(tau), L, _p(x_hist), _p(scen), _p(beh), M,
+                                       _p(x_cand), _p(cscen), _p(cbeh), _p(yh), _p(yc)))
+    return yh, yc

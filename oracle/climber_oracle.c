@@ -750,6 +750,61 @@ int oracle_stack_score(const oracle_cfg *c, const oracle_layer_w *w, const doubl
     return rc;
 }
 
+/*
+ * Training-side form of the "single user, multiple items" pattern (Sec. 3.2): one user's valid
+ * history and ALL its candidates form ONE packed sequence of L + M rows that runs through every
+ * layer under the mask of that section -- history rows see their own subsequence (j <= i as well
+ * when causal), a candidate row sees the whole history and itself, never another candidate -- with
+ * no cache anywhere.  The plain definition: the (L+M) x (L+M) visibility matrix is written out and
+ * every layer is oracle_layer_masked on the whole sequence.
+ * x_hist: [L][d] valid rows only; x_cand: [M][d]; tau: [n_layers][n_scen][n_beh];
+ * y_hist (nullable): [L][d]; y_cand: [M][d].
+ */
+int oracle_stack_packed(const oracle_cfg *c, const oracle_layer_w *w, const double *tau, int L,
+                        const double *x_hist, const int32_t *scen, const int32_t *beh, int M,
+                        const double *x_cand, const int32_t *cscen, const int32_t *cbeh,
+                        double *y_hist, double *y_cand)
+{
+    const int d = c->d_model, n = L + M;
+    double *x = malloc(sizeof(double) * (size_t)n * d);
+    double *y = malloc(sizeof(double) * (size_t)n * d);
+    double *trow = malloc(sizeof(double) * (size_t)n);
+    uint8_t *vis = calloc((size_t)n * n, 1);
+    int rc = ORACLE_OK;
+    if (!x || !y || !trow || !vis) {
+        rc = ORACLE_ERR_ALLOC;
+    } else {
+        memcpy(x, x_hist, sizeof(double) * (size_t)L * d);
+        memcpy(x + (size_t)L * d, x_cand, sizeof(double) * (size_t)M * d);
+        for (int i = 0; i < L; ++i)
+            for (int j = 0; j < L; ++j) {
+                int same = c->sub_len > 0 ? (i / c->sub_len == j / c->sub_len) : 1;
+                vis[(size_t)i * n + j] = (uint8_t)(same && (!c->causal || j <= i));
+            }
+        for (int i = L; i < n; ++i) {
+            for (int j = 0; j < L; ++j)
+                vis[(size_t)i * n + j] = 1;
+            vis[(size_t)i * n + i] = 1;   /* itself; every other candidate stays invisible */
+        }
+        for (int l = 0; l < c->n_layers && !rc; ++l) {
+            const double *tl = tau + (size_t)l * c->n_scen * c->n_beh;
+            for (int i = 0; i < n && !rc; ++i)
+                rc = lookup_tau(tl, c->n_scen, c->n_beh, i < L ? scen[i] : cscen[i - L],
+                                i < L ? beh[i] : cbeh[i - L], &trow[i]);
+            if (!rc)
+                rc = oracle_layer_masked(c, &w[l], n, x, trow, vis, y, NULL, NULL);
+            double *tmp = x; x = y; y = tmp;
+        }
+        if (!rc) {
+            if (y_hist)
+                memcpy(y_hist, x, sizeof(double) * (size_t)L * d);
+            memcpy(y_cand, x + (size_t)L * d, sizeof(double) * (size_t)M * d);
+        }
+    }
+    free(x); free(y); free(trow); free(vis);
+    return rc;
+}
+
 int oracle_num_threads(void)
 {
     int n = 1;

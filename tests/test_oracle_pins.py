@@ -580,3 +580,40 @@ def test_bias_brute_force_python_loops_and_bucket_edges():
         bs = [bias(sc, bh, 12 - j, int(w["cand_ts"][c]) - int(w["hist_ts"][j])) for j in range(12)] + [bias(sc, bh, 0, 0)]
         ref = attend(w["qc"][c, 0], keys, vals, bs, float(w["tau"][sc, bh]))
         assert np.abs(got_c[c] - np.array(ref)).max() < 1e-12
+
+
+# ---------------------------------------------- training-side packed forward (Sec. 3.2 mask, no cache)
+@pytest.mark.parametrize("causal", [False, True])
+def test_packed_forward_equals_cached_path_bruteforce_and_library_composition(causal):
+    # one packed sequence [history; all candidates] under the SUMI mask == encode + score against the
+    # cache == every candidate appended alone; and == the layer composed from library routines with the
+    # mask written out here (candidates mutually invisible: an identity block in the mask)
+    spec, w, cfg = tiny_stack(23, causal=causal, M=4)
+    kc, vc, yh = oracle.stack_encode(cfg, w["layers"], w["tau"], w["tok_off"], w["hist_len"], w["x_hist"],
+                                     w["scen"], w["beh"])
+    y = oracle.stack_score(cfg, w["layers"], w["tau"], w["tok_off"], w["hist_len"], kc, vc, w["cand_off"],
+                           w["x_cand"], w["cscen"], w["cbeh"])
+    L, S = spec.L, spec.sub_len
+    for b in range(spec.B):
+        t0, c0, c1 = w["tok_off"][b], w["cand_off"][b], w["cand_off"][b + 1]
+        ph, pc = oracle.stack_packed(cfg, w["layers"], w["tau"], w["x_hist"][t0:t0 + L], w["scen"][t0:t0 + L],
+                                     w["beh"][t0:t0 + L], w["x_cand"][c0:c1], w["cscen"][c0:c1], w["cbeh"][c0:c1])
+        assert np.abs(pc - y[c0:c1]).max() < 1e-12 and np.abs(ph - yh[t0:t0 + L]).max() < 1e-12
+        bf = oracle.stack_bruteforce(cfg, w["layers"], w["tau"], w["x_hist"][t0:t0 + L], w["scen"][t0:t0 + L],
+                                     w["beh"][t0:t0 + L], w["x_cand"][c0], w["cscen"][c0], w["cbeh"][c0])
+        assert np.abs(bf - pc[0]).max() < 1e-12
+        M = c1 - c0
+        n = L + M
+        i = np.arange(L)
+        vis = np.zeros((n, n), bool)
+        vis[:L, :L] = (i[:, None] // S) == (i[None, :] // S)
+        if causal:
+            vis[:L, :L] &= i[None, :] <= i[:, None]
+        vis[L:, :L] = True
+        vis[L:, L:] = np.eye(M, dtype=bool)
+        x = np.concatenate([w["x_hist"][t0:t0 + L], w["x_cand"][c0:c1]]).astype(np.float64)
+        for l in range(cfg.n_layers):
+            tau_r = np.concatenate([w["tau"][l][w["scen"][t0:t0 + L], w["beh"][t0:t0 + L]],
+                                    w["tau"][l][w["cscen"][c0:c1], w["cbeh"][c0:c1]]])
+            x, _, _ = torch_layer(cfg, w["layers"][l], x, tau_r, vis)
+        assert np.abs(x[L:] - pc).max() < 1e-11 and np.abs(x[:L] - ph).max() < 1e-11
