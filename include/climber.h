@@ -292,6 +292,25 @@ int climber_sumi_score(const climber_config *cfg, const climber_weights *weights
                        const int32_t *cand_beh, float *y_cand, void *workspace, size_t ws_bytes,
                        void *stream);
 
+/* Training-side form of the "single user, multiple items" pattern (Sec. 3.2): the histories and the
+ * candidates of a batch run through all layers TOGETHER as one packed set of rows under the mask of
+ * that section (history rows: own subsequence; a candidate: its user's whole history and itself,
+ * never another candidate) and nothing is cached across calls -- the forward pass behind the
+ * paper's training-throughput figure.  Same result as climber_history_encode followed by
+ * climber_sumi_score; one projection launch per layer covers both kinds of rows, and the history
+ * keys / values of the layer being computed live in layer 0 of `scratch_cache` (a cache handle
+ * created for this batch's histories with any number of layers; its layer 0 is overwritten).
+ * y_hist: dev fp32 [rows][d_model] or NULL (then the last layer skips the history rows' attention
+ * and feed-forward); y_cand: dev fp32 [m_total][d_model].  workspace must hold
+ * climber_workspace_bytes(cfg, rows + m_total).  Candidate counts may differ per user (cand_off).
+ * Errors as climber_history_encode / climber_sumi_score. */
+int climber_sumi_forward(const climber_config *cfg, const climber_weights *weights, const float *tau,
+                         const void *x_hist, const int32_t *scen, const int32_t *beh,
+                         const void *x_cand, const int32_t *cand_off, int32_t m_total, int32_t m_max,
+                         const int32_t *cand_scen, const int32_t *cand_beh,
+                         climber_kv_cache *scratch_cache, float *y_hist, float *y_cand,
+                         void *workspace, size_t ws_bytes, void *stream);
+
 /* climber_sumi_score for callers that cannot allocate or hand over device memory for scratch: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * same kernels and bitwise the same y_cand as climber_sumi_score, but the scratch lives in a fixed

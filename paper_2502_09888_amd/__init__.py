@@ -9,7 +9,7 @@ from .climber import (BAD_BEH, BAD_M_MAX, BAD_OFFSETS, BAD_SCEN, BAD_TAU, BF16, 
                       climber_history_encode, climber_kv_cache_bytes, climber_kv_cache_create,
                       climber_kv_cache_destroy, climber_kv_cache_rows, climber_layer_forward, climber_pack_weights,
                       climber_packed_weights_bytes,
-                      climber_strerror, climber_sumi_score, climber_sumi_score_static, climber_workspace_bytes, library_path,
+                      climber_strerror, climber_sumi_forward, climber_sumi_score, climber_sumi_score_static, climber_workspace_bytes, library_path,
                       load_library)
 
 __all__ = [n for n in dir() if not n.startswith("_")]

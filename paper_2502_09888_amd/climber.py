@@ -104,6 +104,9 @@ def load_library():
     lib.climber_sumi_score.restype = C.c_int
     lib.climber_sumi_score.argtypes = [cfgp, C.POINTER(_Weights), vp, vp, vp, vp, i32, i32, vp,
                                        vp, vp, vp, sz, vp]
+    lib.climber_sumi_forward.restype = C.c_int
+    lib.climber_sumi_forward.argtypes = [cfgp, C.POINTER(_Weights), vp, vp, vp, vp, vp, vp, i32, i32, vp, vp,
+                                         vp, vp, vp, vp, sz, vp]
     lib.climber_sumi_score_static.restype = C.c_int
     lib.climber_sumi_score_static.argtypes = [cfgp, C.POINTER(_Weights), vp, vp, vp, vp, i32, i32, vp,
                                               vp, vp, vp]
@@ -303,3 +306,15 @@ def climber_attn_sumi_bias(cfg: Config, tau_layer, cache: KVCache, layer: int, q
                                               _ptr(k_c), _ptr(v_c), _ptr(cand_off), m_total, m_max,
                                               _ptr(cand_scen), _ptr(cand_beh), _ptr(o_c), C.byref(bias),
                                               _stream(stream)), "climber_attn_sumi_bias")
+
+
+def climber_sumi_forward(cfg: Config, layers, tau, x_hist, scen, beh, x_cand, cand_off, m_total: int,
+                         m_max: int, cand_scen, cand_beh, scratch_cache: KVCache, y_hist, y_cand, workspace,
+                         stream=None, packed=None) -> None:
+    """Training-side packed forward: histories and candidates together, no cache kept."""
+    w, keep = _weights_struct(layers, packed)
+    _ok(load_library().climber_sumi_forward(
+        C.byref(cfg), C.byref(w), _ptr(tau), _ptr(x_hist), _ptr(scen), _ptr(beh), _ptr(x_cand),
+        _ptr(cand_off), m_total, m_max, _ptr(cand_scen), _ptr(cand_beh), scratch_cache.handle,
+        _ptr(y_hist), _ptr(y_cand), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)), "climber_sumi_forward")

@@ -239,6 +239,16 @@ int check_stack_call(const climber_config *cfg, const climber_kv_cache *cache, i
     return check_cache_use(cfg, cache, layer);
 }
 
+int check_scratch_cache(const climber_config *cfg, const climber_kv_cache *cache)
+{
+    int e = check_config(cfg);
+    if (e) return e;
+    if (!cache) return CLIMBER_ERR_NULL;
+    climber_config one = cache->cfg;
+    one.n_layers = cfg->n_layers;
+    return same_config(*cfg, one) ? CLIMBER_OK : CLIMBER_ERR_SHAPE;
+}
+
 }  // namespace climber
 
 // ---- C ABI ------------------------------------------------------------------------------------

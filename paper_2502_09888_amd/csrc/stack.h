@@ -29,5 +29,8 @@ struct QkvToCache;
 bool cache_direct_target(const climber_config *cfg, climber_kv_cache *cache, int32_t layer, QkvToCache *out);
 int64_t cache_rows(const climber_kv_cache *c);
 int check_stack_call(const climber_config *cfg, const climber_kv_cache *cache, int32_t layer);
+// the same for a call that only uses layer 0 of the cache as scratch: the cache may have been created
+// for any number of layers
+int check_scratch_cache(const climber_config *cfg, const climber_kv_cache *cache);
 
 }  // namespace climber

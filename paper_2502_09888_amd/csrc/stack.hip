@@ -351,6 +351,75 @@ int climber_history_encode(const climber_config *cfg, const climber_weights *wei
     return CLIMBER_OK;
 }
 
+int climber_sumi_forward(const climber_config *cfg, const climber_weights *weights, const float *tau,
+                         const void *x_hist, const int32_t *scen, const int32_t *beh, const void *x_cand,
+                         const int32_t *cand_off, int32_t m_total, int32_t m_max,
+                         const int32_t *cand_scen, const int32_t *cand_beh, climber_kv_cache *scratch_cache,
+                         float *y_hist, float *y_cand, void *workspace, size_t ws_bytes, void *stream)
+{
+    TRY(check_stack_config(cfg));
+    TRY(check_scratch_cache(cfg, scratch_cache));
+    if (!tau || !x_hist || !scen || !beh || !x_cand || !cand_scen || !cand_beh || !y_cand || !workspace)
+        return CLIMBER_ERR_NULL;
+    TRY(check_weights(cfg, weights));
+    TRY(check_cand_args(cfg, cand_off, m_total, m_max));
+    const int64_t T = cache_rows(scratch_cache), R = T + m_total;
+    if (R * (int64_t)std::max(cfg->d_ffn, 3 * cfg->d_model) >= (int64_t)1 << 31) return CLIMBER_ERR_RANGE;
+    if ((uintptr_t)workspace % 256 != 0 || (uintptr_t)x_hist % 16 != 0 || (uintptr_t)x_cand % 16 != 0 ||
+        (uintptr_t)y_cand % 16 != 0 || (uintptr_t)y_hist % 16 != 0)
+        return CLIMBER_ERR_ALIGN;
+    Workspace ws = carve(cfg, R, workspace);
+    if (ws_bytes < ws.total) return CLIMBER_ERR_BUFSIZE;
+    if (R == 0) return CLIMBER_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const int d = cfg->d_model, F = cfg->d_ffn, np = d / 64;
+    TRY(stage_weights(cfg, weights, ws, s));
+    // rows [0, T): the padded history rows of the batch; rows [T, R): the candidates
+    TRY(rt(row_prep_bf16(x_hist, ws.x32, ws.ss, np, T, d, s)));
+    TRY(rt(row_prep_bf16(x_cand, ws.x32 + (size_t)T * d, ws.ss + (size_t)T * np, np, m_total, d, s)));
+    if (T) TRY(rt(hipMemcpyAsync(ws.xb, x_hist, (size_t)T * d * 2, hipMemcpyDeviceToDevice, s)));
+    if (m_total)
+        TRY(rt(hipMemcpyAsync(ws.xb + (size_t)T * d * 2, x_cand, (size_t)m_total * d * 2, hipMemcpyDeviceToDevice, s)));
+    const RowNormIn nin{ws.ss, np, 1.f / (float)d, cfg->rms_eps}, no_in{nullptr, 0, 0.f, 0.f};
+    const RowNormOut no_out{nullptr, nullptr, 0};
+    const size_t tl = (size_t)cfg->n_scen * cfg->n_beh;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const bool last = l + 1 == cfg->n_layers;
+        const PackedLayer pw = packed_layer(cfg, ws, l);
+        const float *tau_l = tau + l * tl;
+        // one fused projection over both kinds of rows
+        TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xb, d, pw.wqkv, (int)R, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, nin, no_out, 0,
+                         s)));
+        const uint8_t *q = ws.qkv, *k = q + (size_t)d * 2, *v = q + (size_t)2 * d * 2;
+        const size_t crow = (size_t)T * 3 * d * 2;  // first candidate row of the projection output
+        // the history's outputs of the last layer feed nothing unless the caller wants them
+        const bool hist_out = !last || y_hist;
+        // history rows: keys / values into layer 0 of the scratch cache, attention inside the subsequences
+        TRY(attn_history_strided(cfg, tau_l, q, k, v, 3 * d, scen, beh, scratch_cache, 0, hist_out ? ws.o : nullptr, d,
+                                 s));
+        // candidate rows: the whole history of this layer plus themselves
+        TRY(attn_sumi_strided(cfg, tau_l, scratch_cache, 0, q + crow, k + crow, v + crow, 3 * d, cand_off, m_total,
+                              m_max, cand_scen, cand_beh, ws.o + (size_t)T * d * 2, d, s));
+        // output projection and feed-forward on the rows that go on: all of them, or the candidates only
+        const int64_t r0 = hist_out ? 0 : T, nr = R - r0;
+        if (nr == 0) continue;
+        const RowNormIn nin_r{ws.ss + (size_t)r0 * np, np, 1.f / (float)d, cfg->rms_eps};
+        const RowNormOut nout_r{ws.ss + (size_t)r0 * np, ws.xb + (size_t)r0 * d * 2, d};
+        float *x_r = ws.x32 + (size_t)r0 * d, *h_r = ws.h32 + (size_t)r0 * d;
+        uint8_t *u_r = ws.u + (size_t)r0 * F * 2;  // r0 is a multiple of 64: whole groups of 16 rows
+        TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o + (size_t)r0 * d * 2, d, pw.wo, (int)nr, d, d, h_r, d, x_r, d, no_in,
+                         nout_r, 0, s)));
+        TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xb + (size_t)r0 * d * 2, d, pw.w1, (int)nr, F, d, u_r, F, nullptr, 0, nin_r,
+                         no_out, kTiledC, s)));
+        TRY(rt(gemm_bf16(EPI_RESID_F32, u_r, F, pw.w2, (int)nr, d, F, x_r, d, h_r, d, no_in, last ? no_out : nout_r,
+                         kTiledA, s)));
+    }
+    if (y_hist && T) TRY(rt(hipMemcpyAsync(y_hist, ws.x32, (size_t)T * d * 4, hipMemcpyDeviceToDevice, s)));
+    if (m_total)
+        TRY(rt(hipMemcpyAsync(y_cand, ws.x32 + (size_t)T * d, (size_t)m_total * d * 4, hipMemcpyDeviceToDevice, s)));
+    return CLIMBER_OK;
+}
+
 int climber_sumi_score(const climber_config *cfg, const climber_weights *weights, const float *tau,
                        const climber_kv_cache *cache, const void *x_cand, const int32_t *cand_off,
                        int32_t m_total, int32_t m_max, const int32_t *cand_scen,
