@@ -326,3 +326,21 @@ def stack_packed(cfg: StackConfig, layers, tau, x_hist, scen, beh, x_cand, cscen
     _check(_load().oracle_stack_packed(C.byref(cc), w, _p(tau), L, _p(x_hist), _p(scen), _p(beh), M,
                                        _p(x_cand), _p(cscen), _p(cbeh), _p(yh), _p(yc)))
     return yh, yc
+
+
+def bgf(cfg: StackConfig, atl_layer: dict, tau_scen, w_down, w_up, w_head, b_head, e, scen):
+    """Bit-wise gating fusion (Eq. (4)) + linear head for m candidates.  e: [m, N_b, d] block outputs;
+    scen: [m].  Returns (G [m, N_b, d], Y [m, N_b, d], score [m])."""
+    c1 = StackConfig(**{**cfg.__dict__, "n_layers": 1})
+    w, keep = _weights(c1, [atl_layer])
+    tau_scen, w_down, w_up, w_head, e = _f64(tau_scen), _f64(w_down), _f64(w_up), _f64(w_head), _f64(e)
+    scen = _i32(scen)
+    m, nb, d = e.shape
+    dg = w_down.shape[1]
+    assert d == cfg.d_model and w_down.shape == (nb * d, dg) and w_up.shape == (dg, nb * d)
+    assert w_head.shape == (nb * d,) and scen.shape == (m,)
+    g, y, sc = np.empty_like(e), np.empty_like(e), np.empty(m)
+    cc = c1._c()
+    _check(_load().oracle_bgf(C.byref(cc), w, _p(tau_scen), len(tau_scen), nb, dg, _p(w_down), _p(w_up),
+                              _p(w_head), C.c_double(b_head), m, _p(e), _p(scen), _p(g), _p(y), _p(sc)))
+    return g, y, sc

@@ -805,6 +805,81 @@ int oracle_stack_packed(const oracle_cfg *c, const oracle_layer_w *w, const doub
     return rc;
 }
 
+/*
+ * Bit-wise gating fusion, Sec. 3.1.4, Eq. (4), for m candidates at once:
+ *   E(S) = the N_b block outputs of a candidate, [N_b][d]
+ *   G(S) = ATL(E(S)): one attention layer over those N_b rows, every row seeing every row, WITHOUT
+ *          relative attention bias and with a temperature that depends on the scenario only
+ *   Y(S) = G(S) (.) sigmoid(f_gate(G(S))),  f_gate = squeeze-and-excitation with equal input and
+ *          output dimensions
+ *   score = "subsequent network"(Y(S))
+ * What the paper leaves open, as fixed by this build (readings): the fusion ATL has the layer
+ * composition of every other layer here (pre-RMSNorm, fused QKV, output projection, residuals,
+ * erf-GELU feed-forward) with weights of its own; f_gate acts on the N_b*d values of G flattened
+ * row by row: down-projection to d_gate, ReLU, up-projection back to N_b*d, no bias vectors; the
+ * subsequent network is one linear map of the flattened Y(S) plus a scalar offset.
+ * e: [m][N_b][d]; scen: [m]; tau_scen: [n_scen]; w_down: [N_b*d][d_gate]; w_up: [d_gate][N_b*d];
+ * w_head: [N_b*d]; g_out, y_out (nullable): [m][N_b][d]; score: [m].
+ */
+int oracle_bgf(const oracle_cfg *c, const oracle_layer_w *w_atl, const double *tau_scen, int n_scen,
+               int n_blocks, int d_gate, const double *w_down, const double *w_up,
+               const double *w_head, double b_head, int m, const double *e, const int32_t *scen,
+               double *g_out, double *y_out, double *score)
+{
+    const int d = c->d_model, nb = n_blocks;
+    const size_t nd = (size_t)nb * d;
+    int rc = ORACLE_OK;
+    if (nb < 1 || d_gate < 1)
+        return ORACLE_ERR_ID;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int i = 0; i < m; ++i) {
+        double *g = malloc(sizeof(double) * nd), *hid = malloc(sizeof(double) * (size_t)d_gate);
+        double *trow = malloc(sizeof(double) * (size_t)nb);
+        uint8_t *vis = malloc((size_t)nb * nb);
+        int e_ = ORACLE_OK;
+        if (!g || !hid || !trow || !vis) {
+            e_ = ORACLE_ERR_ALLOC;
+        } else if (scen[i] < 0 || scen[i] >= n_scen) {
+            e_ = ORACLE_ERR_ID;
+        } else {
+            const double t = tau_scen[scen[i]];
+            if (!(t > 0.0) || isinf(t) || isnan(t))
+                e_ = ORACLE_ERR_TAU;
+            for (int r = 0; r < nb; ++r)
+                trow[r] = t;
+            memset(vis, 1, (size_t)nb * nb);
+            if (!e_)
+                e_ = oracle_layer_masked(c, w_atl, nb, e + (size_t)i * nd, trow, vis, g, NULL, NULL);
+        }
+        if (!e_) {
+            for (int j = 0; j < d_gate; ++j) {
+                double acc = 0.0;
+                for (size_t k = 0; k < nd; ++k)
+                    acc += g[k] * w_down[k * d_gate + j];
+                hid[j] = acc > 0.0 ? acc : 0.0;
+            }
+            double sc = b_head;
+            for (size_t k = 0; k < nd; ++k) {
+                double acc = 0.0;
+                for (int j = 0; j < d_gate; ++j)
+                    acc += hid[j] * w_up[(size_t)j * nd + k];
+                const double yk = g[k] * (1.0 / (1.0 + exp(-acc)));
+                if (g_out)
+                    g_out[(size_t)i * nd + k] = g[k];
+                if (y_out)
+                    y_out[(size_t)i * nd + k] = yk;
+                sc += yk * w_head[k];
+            }
+            score[i] = sc;
+        } else {
+#pragma omp atomic write
+            rc = e_;
+        }
+        free(g); free(hid); free(trow); free(vis);
+    }
+    return rc;
+}
+
 int oracle_num_threads(void)
 {
     int n = 1;

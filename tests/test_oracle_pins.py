@@ -617,3 +617,65 @@ def test_packed_forward_equals_cached_path_bruteforce_and_library_composition(ca
                                     w["tau"][l][w["cscen"][c0:c1], w["cbeh"][c0:c1]]])
             x, _, _ = torch_layer(cfg, w["layers"][l], x, tau_r, vis)
         assert np.abs(x[L:] - pc).max() < 1e-11 and np.abs(x[:L] - ph).max() < 1e-11
+
+
+# ------------------------------------------------------------ bit-wise gating fusion, Eq. (4)
+def tiny_bgf(seed, nb=3, m=5, dg=6):
+    spec = W.StackSpec("tiny-bgf", B=1, L=4, sub_len=0, M=1, n_layers=1, d_model=8, H=2, dh=4, d_ffn=12,
+                       n_scen=3, n_beh=2, w_std=0.3, pad_to=4, seed=seed)
+    cfg = oracle.StackConfig(1, 8, 2, 4, 12, 3, 2, qk_scale=0.5)
+    return spec, cfg, W.make_bgf(spec, nb, dg, m)
+
+
+def test_bgf_against_library_composition_and_layer_masked():
+    spec, cfg, w = tiny_bgf(41)
+    g, y, sc = oracle.bgf(cfg, w["atl"], w["tau_scen"], w["w_down"], w["w_up"], w["w_head"], w["b_head"], w["e"],
+                          w["scen"])
+    nb = w["n_blocks"]
+    for i in range(w["e"].shape[0]):
+        tau_r = np.full(nb, float(w["tau_scen"][w["scen"][i]]))
+        vis = np.ones((nb, nb), bool)
+        gl, _, _ = oracle.layer_masked(cfg, w["atl"], w["e"][i], tau_r, vis)
+        gt, _, _ = torch_layer(cfg, w["atl"], w["e"][i], tau_r, vis)
+        assert np.array_equal(gl, g[i]) and np.abs(gt - g[i]).max() < 1e-12
+        G = torch.from_numpy(g[i].reshape(-1))
+        gate = torch.sigmoid(torch.relu(G @ torch.from_numpy(w["w_down"].astype(np.float64))) @
+                             torch.from_numpy(w["w_up"].astype(np.float64)))
+        yr = (G * gate).numpy()
+        assert np.abs(yr - y[i].reshape(-1)).max() < 1e-13
+        assert abs(float(yr @ w["w_head"].astype(np.float64)) + w["b_head"] - sc[i]) < 1e-12
+
+
+def test_bgf_closed_forms():
+    spec, cfg, w = tiny_bgf(42)
+    args = (w["tau_scen"], w["w_down"], w["w_up"], w["w_head"], w["b_head"])
+    g, y, sc = oracle.bgf(cfg, w["atl"], *args, w["e"], w["scen"])
+    # a zero up-projection: every gate is sigmoid(0) = 1/2
+    g0, y0, sc0 = oracle.bgf(cfg, w["atl"], w["tau_scen"], w["w_down"], np.zeros_like(w["w_up"]), w["w_head"],
+                             w["b_head"], w["e"], w["scen"])
+    assert np.array_equal(g0, g) and np.abs(y0 - 0.5 * g).max() < 1e-15
+    assert np.abs(sc0 - (0.5 * g.reshape(len(sc), -1) @ w["w_head"].astype(np.float64) + w["b_head"])).max() < 1e-12
+    # the temperature depends on the scenario only, and matters
+    other = (w["scen"] + 1) % 3
+    assert np.abs(oracle.bgf(cfg, w["atl"], *args, w["e"], other)[0] - g).max() > 1e-4
+    # blocks interact through the fusion attention only: with a zero output projection G = FFN-residual of
+    # each row on its own, so permuting the blocks of a candidate permutes the rows of G
+    atl0 = dict(w["atl"], Wo=np.zeros_like(w["atl"]["Wo"]))
+    perm = np.array([2, 0, 1])
+    ga = oracle.bgf(cfg, atl0, *args, w["e"], w["scen"])[0]
+    gb = oracle.bgf(cfg, atl0, *args, w["e"][:, perm], w["scen"])[0]
+    assert np.abs(gb - ga[:, perm]).max() < 1e-13
+    # ... and with it, they do interact: the attention of the fusion layer is permutation-equivariant too
+    gc = oracle.bgf(cfg, w["atl"], *args, w["e"][:, perm], w["scen"])[0]
+    assert np.abs(gc - g[:, perm]).max() < 1e-12 and np.abs(ga - g).max() > 1e-3
+    # one block: softmax over a single key is 1, the attention output is the value row itself
+    spec1, cfg1, w1 = tiny_bgf(43, nb=1)
+    g1 = oracle.bgf(cfg1, w1["atl"], w1["tau_scen"], w1["w_down"], w1["w_up"], w1["w_head"], w1["b_head"], w1["e"],
+                    w1["scen"])[0]
+    for i in range(len(g1)):
+        x = torch.from_numpy(w1["e"][i].astype(np.float64))
+        t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+        v = (F.rms_norm(x, (8,), t(w1["atl"]["g1"]), eps=cfg1.rms_eps) @ t(w1["atl"]["Wqkv"]))[:, 16:]
+        h = x + v @ t(w1["atl"]["Wo"])
+        ref = h + F.gelu(F.rms_norm(h, (8,), t(w1["atl"]["g2"]), eps=cfg1.rms_eps) @ t(w1["atl"]["W1"])) @ t(w1["atl"]["W2"])
+        assert np.abs(ref.numpy() - g1[i]).max() < 1e-12

@@ -218,3 +218,27 @@ def add_bias_inputs(w: dict, n_pos: int = 33, n_time: int = 12, table_std: float
              pos_table=(rng.standard_normal((spec.n_scen, spec.n_beh, H, n_pos)) * table_std).astype(np.float32),
              time_table=(rng.standard_normal((spec.n_scen, spec.n_beh, H, n_time)) * table_std).astype(np.float32))
     return w
+
+
+def make_bgf(spec: StackSpec, n_blocks: int, d_gate: int, m: int, seed: int = 11) -> dict:
+    """Random inputs of the fusion module (Eq. (4)): block outputs e [m, n_blocks, d] ~ N(0,1) (the
+    scale of the stack's hidden states), scenario ids, the fusion layer's weights (drawn like a stack
+    layer's), gate and head weights, a scenario-only temperature table.  bf16-representable where
+    the library takes bf16."""
+    rng = _rng(spec.seed * 977 + seed)
+    d, F = spec.d_model, spec.d_ffn
+    nd = n_blocks * d
+    lw = {}
+    for name, shp in (("g1", (d,)), ("Wqkv", (d, 3 * d)), ("Wo", (d, d)), ("g2", (d,)), ("W1", (d, F)),
+                      ("W2", (F, d))):
+        a = rng.standard_normal(shp, dtype=np.float32) * np.float32(spec.w_std)
+        if name in ("g1", "g2"):
+            a = a + np.float32(1.0)
+        lw[name] = round_bf16(a)
+    return dict(spec=spec, n_blocks=n_blocks, d_gate=d_gate, atl=lw,
+                e=rng.standard_normal((m, n_blocks, d), dtype=np.float32),
+                scen=rng.integers(0, spec.n_scen, size=m).astype(np.int32),
+                tau_scen=rng.uniform(0.5, 2.0, size=spec.n_scen).astype(np.float32),
+                w_down=round_bf16(rng.standard_normal((nd, d_gate), dtype=np.float32) * np.float32(nd ** -0.5)),
+                w_up=round_bf16(rng.standard_normal((d_gate, nd), dtype=np.float32) * np.float32(2.0 * d_gate ** -0.5)),
+                w_head=(rng.standard_normal(nd) * nd ** -0.5).astype(np.float32), b_head=0.25)
