@@ -311,6 +311,40 @@ int climber_sumi_forward(const climber_config *cfg, const climber_weights *weigh
                          climber_kv_cache *scratch_cache, float *y_hist, float *y_cand,
                          void *workspace, size_t ws_bytes, void *stream);
 
+/* ---- bit-wise gating fusion (Sec. 3.1.4, Eq. (4)) and score ------------------------------------
+ * The paper runs one Transformer block per subsequence ("corresponding block", Sec. 3.1.2); block k
+ * turns a candidate into an output vector E(S_k), and the fusion module turns the N_b vectors of a
+ * candidate into its score:
+ *     G = ATL(E)                     one attention layer over the N_b rows of the candidate, every row
+ *                                    seeing every row, no relative attention bias, temperature from the
+ *                                    candidate's scenario only (tau_scen[scen])
+ *     Y = G (.) sigmoid(f_gate(G))   f_gate: squeeze-and-excitation with equal input / output size
+ *     score = head(Y)
+ * As fixed by this library where the paper is silent: the fusion ATL is a layer of the stack's
+ * composition (see climber_layer_weights) with weights of its own; f_gate maps the N_b * d_model
+ * values of G, flattened row by row, down to d_gate, applies ReLU, and maps back (no bias vectors);
+ * the head is <w_head, vec(Y)> + b_head.  Block k's E(S_k) is produced with the calls above: a
+ * cache over subsequence k only (sub_len = 0), block k's weights, climber_history_encode, then
+ * climber_sumi_score or climber_sumi_forward: its y_cand rows are E(S_k).
+ * e: dev fp32 [m_total][n_blocks][d_model]; cand_scen: dev int32 [m_total]; y: dev fp32 like e, or
+ * NULL; score: dev fp32 [m_total].  CLIMBER_BF16, d_head = 64, 1 <= n_blocks <= 16, d_gate a
+ * multiple of 128 and <= n_blocks * d_model.  workspace: climber_bgf_workspace_bytes(), 256-byte
+ * aligned.  Errors: CLIMBER_ERR_NULL, _SHAPE, _UNSUPPORTED, _ALIGN, _RANGE, _BUFSIZE, _RUNTIME. */
+typedef struct climber_bgf_weights {
+    climber_layer_weights atl; /* fusion layer, bf16, shapes of a stack layer */
+    const void *w_down;        /* dev bf16 [n_blocks * d_model][d_gate] */
+    const void *w_up;          /* dev bf16 [d_gate][n_blocks * d_model] */
+    const float *w_head;       /* dev fp32 [n_blocks * d_model] */
+    const float *tau_scen;     /* dev fp32 [n_scen] */
+    float b_head;
+    int32_t n_blocks, d_gate;
+} climber_bgf_weights;
+size_t climber_bgf_workspace_bytes(const climber_config *cfg, int32_t n_blocks, int32_t d_gate,
+                                   int64_t m_total);
+int climber_bgf_score(const climber_config *cfg, const climber_bgf_weights *w, const float *e,
+                      const int32_t *cand_scen, int32_t m_total, float *y, float *score,
+                      void *workspace, size_t ws_bytes, void *stream);
+
 /* climber_sumi_score for callers that cannot allocate or hand over device memory for scratch: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * same kernels and bitwise the same y_cand as climber_sumi_score, but the scratch lives in a fixed

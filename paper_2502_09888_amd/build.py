@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libclimber.so")
 SOURCES = ["climber_api.hip", "attn_bf16.hip", "attn_f32.hip", "kv_cache.hip", "stack.hip",
-           "gemm_bf16.hip", "rowwise.hip", "hist_fused_bf16.hip", "check.hip"]
+           "gemm_bf16.hip", "rowwise.hip", "hist_fused_bf16.hip", "check.hip", "bgf.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

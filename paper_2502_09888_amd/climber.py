@@ -45,6 +45,12 @@ class RelBias(C.Structure):
                 ("cand_pos", C.c_void_p), ("cand_ts", C.c_void_p)]
 
 
+class BgfWeights(C.Structure):
+    """Mirror of ``climber_bgf_weights``."""
+    _fields_ = [("atl", LayerWeights), ("w_down", C.c_void_p), ("w_up", C.c_void_p), ("w_head", C.c_void_p),
+                ("tau_scen", C.c_void_p), ("b_head", C.c_float), ("n_blocks", C.c_int32), ("d_gate", C.c_int32)]
+
+
 class _Weights(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(LayerWeights)), ("packed", C.c_void_p)]
 
@@ -104,6 +110,10 @@ def load_library():
     lib.climber_sumi_score.restype = C.c_int
     lib.climber_sumi_score.argtypes = [cfgp, C.POINTER(_Weights), vp, vp, vp, vp, i32, i32, vp,
                                        vp, vp, vp, sz, vp]
+    lib.climber_bgf_workspace_bytes.restype = sz
+    lib.climber_bgf_workspace_bytes.argtypes = [cfgp, i32, i32, i64]
+    lib.climber_bgf_score.restype = C.c_int
+    lib.climber_bgf_score.argtypes = [cfgp, C.POINTER(BgfWeights), vp, vp, i32, vp, vp, vp, sz, vp]
     lib.climber_sumi_forward.restype = C.c_int
     lib.climber_sumi_forward.argtypes = [cfgp, C.POINTER(_Weights), vp, vp, vp, vp, vp, vp, i32, i32, vp, vp,
                                          vp, vp, vp, vp, sz, vp]
@@ -318,3 +328,17 @@ def climber_sumi_forward(cfg: Config, layers, tau, x_hist, scen, beh, x_cand, ca
         _ptr(cand_off), m_total, m_max, _ptr(cand_scen), _ptr(cand_beh), scratch_cache.handle,
         _ptr(y_hist), _ptr(y_cand), _ptr(workspace), workspace.numel() * workspace.element_size(),
         _stream(stream)), "climber_sumi_forward")
+
+
+def climber_bgf_workspace_bytes(cfg: Config, n_blocks: int, d_gate: int, m_total: int) -> int:
+    return int(load_library().climber_bgf_workspace_bytes(C.byref(cfg), n_blocks, d_gate, m_total))
+
+
+def climber_bgf_score(cfg: Config, atl_layer, w_down, w_up, w_head, tau_scen, b_head: float, n_blocks: int,
+                      d_gate: int, e, cand_scen, m_total: int, y, score, workspace, stream=None) -> None:
+    """Bit-wise gating fusion (Eq. (4)) + linear head over the candidates' block outputs e."""
+    w = BgfWeights(_layer_struct(atl_layer), _ptr(w_down), _ptr(w_up), _ptr(w_head), _ptr(tau_scen), b_head,
+                   n_blocks, d_gate)
+    _ok(load_library().climber_bgf_score(C.byref(cfg), C.byref(w), _ptr(e), _ptr(cand_scen), m_total, _ptr(y),
+                                         _ptr(score), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                         _stream(stream)), "climber_bgf_score")

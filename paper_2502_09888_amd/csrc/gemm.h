@@ -5,7 +5,7 @@
 
 namespace climber {
 
-enum { EPI_STORE_BF16 = 0, EPI_GELU_BF16 = 1, EPI_RESID_F32 = 2 };
+enum { EPI_STORE_BF16 = 0, EPI_GELU_BF16 = 1, EPI_RESID_F32 = 2, EPI_RELU_BF16 = 3 };
 
 // RMSNorm folded into the projections around it.  A projection whose input is RMSNorm(x; g) runs on
 // the plain bf16 rows of x with the gain folded into the weight rows (pack job with `gain`) and
@@ -61,7 +61,7 @@ struct QkvToCache {         // layer_base == nullptr: plain store
 };
 
 // C = A W (+ epilogue).  A: bf16 [M][lda], or tiled (kTiledA; lda unused); w_packed from pack_weight;
-// N % 128 == 0, K % 64 == 0.  EPI_STORE_BF16 / EPI_GELU_BF16: C is bf16 [M][ldc] (EPI_GELU_BF16 with
+// N % 128 == 0, K % 64 == 0.  EPI_STORE_BF16 / EPI_GELU_BF16 / EPI_RELU_BF16: C is bf16 [M][ldc] (EPI_GELU_BF16 with
 // kTiledC: tiled, ldc unused).  EPI_RESID_F32: C is fp32, C = acc + resid.
 hipError_t gemm_bf16(int epi, const void *A, int64_t lda, const void *w_packed, int M, int N, int K,
                      void *C, int64_t ldc, const float *resid, int64_t ldr, const RowNormIn &in_norm,

@@ -358,7 +358,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float x = acc[i][j][4 * g + e] * rs[i];
-                        v[e] = (__bf16)(EPI == EPI_GELU_BF16 ? gelu_erf(x) : x);
+                        v[e] = (__bf16)(EPI == EPI_GELU_BF16 ? gelu_erf(x) : EPI == EPI_RELU_BF16 ? fmaxf(x, 0.f) : x);
                     }
                     if (EPI == EPI_STORE_BF16 && zero_row[i]) v[0] = v[1] = v[2] = v[3] = (__bf16)0.f;
                     *(uint2 *)(tr + l32 * kPitch + col * 2) = *(const uint2 *)v;
@@ -520,6 +520,7 @@ hipError_t gemm_bf16(int epi, const void *A, int64_t lda, const void *w_packed, 
     case EPI_STORE_BF16: return dispatch<EPI_STORE_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
     case EPI_GELU_BF16: return dispatch<EPI_GELU_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
     case EPI_RESID_F32: return dispatch<EPI_RESID_F32>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
+    case EPI_RELU_BF16: return dispatch<EPI_RELU_BF16>(a, lda, w, M, N, K, C, ldc, resid, ldr, nin, nout, tiled, qc, s);
     default: return hipErrorInvalidValue;
     }
 }

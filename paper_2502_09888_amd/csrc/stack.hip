@@ -13,6 +13,7 @@
 #include <cmath>
 #include <mutex>
 
+#include "bgf.h"
 #include "gemm.h"
 
 using namespace climber;
@@ -349,6 +350,82 @@ int climber_history_encode(const climber_config *cfg, const climber_weights *wei
                       beh, nullptr, 0, 0, rows, ws, s));
     }
     return CLIMBER_OK;
+}
+
+// ---- bit-wise gating fusion (Eq. (4)) -------------------------------------------------------
+// scratch = the stack's scratch for m * n_blocks rows and one layer (the fusion layer) + the packed
+// gate weights
+static size_t bgf_gate_bytes(const climber_config *cfg, int nb, int dg)
+{
+    return up256((size_t)2 * nb * cfg->d_model * dg * 2);
+}
+
+static int check_bgf(const climber_config *cfg, int32_t n_blocks, int32_t d_gate)
+{
+    TRY(check_stack_config(cfg));
+    if (cfg->d_head != 64 || cfg->n_heads * 64 != cfg->d_model) return CLIMBER_ERR_UNSUPPORTED;
+    if (n_blocks < 1 || n_blocks > bgf_max_blocks() || d_gate < 1) return CLIMBER_ERR_SHAPE;
+    if (d_gate % 128 != 0 || d_gate > n_blocks * cfg->d_model) return CLIMBER_ERR_UNSUPPORTED;
+    return CLIMBER_OK;
+}
+
+size_t climber_bgf_workspace_bytes(const climber_config *cfg, int32_t n_blocks, int32_t d_gate, int64_t m_total)
+{
+    if (check_bgf(cfg, n_blocks, d_gate) != CLIMBER_OK || m_total < 0) return 0;
+    climber_config one = *cfg;
+    one.n_layers = 1;
+    return carve(&one, m_total * n_blocks, nullptr).total + bgf_gate_bytes(cfg, n_blocks, d_gate);
+}
+
+int climber_bgf_score(const climber_config *cfg, const climber_bgf_weights *w, const float *e,
+                      const int32_t *cand_scen, int32_t m_total, float *y, float *score, void *workspace,
+                      size_t ws_bytes, void *stream)
+{
+    if (!w) return CLIMBER_ERR_NULL;
+    TRY(check_bgf(cfg, w->n_blocks, w->d_gate));
+    TRY(check_layer_weights(&w->atl));
+    if (!w->w_down || !w->w_up || !w->w_head || !w->tau_scen || !e || !cand_scen || !score || !workspace)
+        return CLIMBER_ERR_NULL;
+    if (m_total < 0) return CLIMBER_ERR_SHAPE;
+    const int nb = w->n_blocks, dg = w->d_gate, d = cfg->d_model, F = cfg->d_ffn, nd = nb * d, np = d / 64;
+    const int64_t R = (int64_t)m_total * nb;
+    if (R * (int64_t)std::max(F, 3 * d) >= (int64_t)1 << 31) return CLIMBER_ERR_RANGE;
+    if ((uintptr_t)workspace % 256 != 0 || (uintptr_t)e % 16 != 0 || (uintptr_t)y % 16 != 0 ||
+        (uintptr_t)w->w_down % 16 != 0 || (uintptr_t)w->w_up % 16 != 0)
+        return CLIMBER_ERR_ALIGN;
+    climber_config one = *cfg;
+    one.n_layers = 1;
+    Workspace ws = carve(&one, R, workspace);
+    uint8_t *gate_pack = (uint8_t *)workspace + ws.total;
+    if (ws_bytes < ws.total + bgf_gate_bytes(cfg, nb, dg)) return CLIMBER_ERR_BUFSIZE;
+    if (m_total == 0) return CLIMBER_OK;
+    hipStream_t s = (hipStream_t)stream;
+    // operand order for the fusion layer's weights (gains folded in) and the two gate projections
+    TRY(pack_layers(&one, &w->atl, 1, ws, s));
+    uint8_t *down_p = gate_pack, *up_p = gate_pack + (size_t)nd * dg * 2;
+    {
+        PackJobs jobs;
+        jobs.n = 2;
+        jobs.w[0] = w->w_down, jobs.gain[0] = nullptr, jobs.packed[0] = down_p, jobs.K[0] = nd, jobs.N[0] = dg;
+        jobs.w[1] = w->w_up, jobs.gain[1] = nullptr, jobs.packed[1] = up_p, jobs.K[1] = dg, jobs.N[1] = nd;
+        TRY(rt(pack_weights(jobs, s)));
+    }
+    const PackedLayer pw = packed_layer(&one, ws, 0);
+    const RowNormIn nin{ws.ss, np, 1.f / (float)d, cfg->rms_eps}, no_in{nullptr, 0, 0.f, 0.f};
+    const RowNormOut nout{ws.ss, ws.xb, d}, no_out{nullptr, nullptr, 0};
+    // G = ATL(E) on the m * n_blocks rows: the layer of the stack with the fusion attention in the middle
+    TRY(rt(row_prep_f32(e, ws.xb, ws.ss, np, R, d, s)));
+    TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xb, d, pw.wqkv, (int)R, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, nin, no_out, 0, s)));
+    TRY(rt(launch_bgf_attention(ws.qkv, ws.o, cand_scen, w->tau_scen, cfg->n_scen, m_total, nb, cfg->n_heads,
+                                cfg->qk_scale, s)));
+    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.o, d, pw.wo, (int)R, d, d, ws.h32, d, e, d, no_in, nout, 0, s)));
+    TRY(rt(gemm_bf16(EPI_GELU_BF16, ws.xb, d, pw.w1, (int)R, F, d, ws.u, F, nullptr, 0, nin, no_out, kTiledC, s)));
+    TRY(rt(gemm_bf16(EPI_RESID_F32, ws.u, F, pw.w2, (int)R, d, F, ws.x32, d, ws.h32, d, no_in, nout, kTiledA, s)));
+    // f_gate on the flattened G (its bf16 copy, [m][n_blocks * d]): down, ReLU, up; then sigmoid,
+    // Hadamard product and the head in one pass over G
+    TRY(rt(gemm_bf16(EPI_RELU_BF16, ws.xb, nd, down_p, m_total, dg, nd, ws.o, dg, nullptr, 0, no_in, no_out, 0, s)));
+    TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.o, dg, up_p, m_total, nd, dg, ws.qkv, nd, nullptr, 0, no_in, no_out, 0, s)));
+    return rt(launch_bgf_gate_head(ws.x32, ws.qkv, w->w_head, w->b_head, y, score, m_total, nd, s));
 }
 
 int climber_sumi_forward(const climber_config *cfg, const climber_weights *weights, const float *tau,

@@ -1,0 +1,98 @@
+"""GPU parity of the bit-wise gating fusion module (Sec. 3.1.4, Eq. (4)) and of the paper-faithful
+multi-block scoring it closes: one block (own weights, own cache) per subsequence, the candidate scored
+against each block on its own, the N_b block outputs fused into a score.  Reference: the oracle's bgf()
+and its stack functions, same seeded inputs; tolerance 2e-2 max-abs (unit-scale values)."""
+import numpy as np
+import pytest
+
+import workloads as W
+from harness import GpuStack, max_abs, oracle, oracle_stack_config, say, stack_config
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_bgf(P, torch, cfg, w, e):
+    dev, bf = "cuda:0", torch.bfloat16
+    m, nb, dg = e.shape[0], w["n_blocks"], w["d_gate"]
+    atl = {n.lower(): torch.from_numpy(w["atl"][n]).to(dev).to(bf).contiguous() for n in ("g1", "Wqkv", "Wo", "g2", "W1", "W2")}
+    wd = torch.from_numpy(w["w_down"]).to(dev).to(bf).contiguous()
+    wu = torch.from_numpy(w["w_up"]).to(dev).to(bf).contiguous()
+    wh = torch.from_numpy(w["w_head"]).to(dev)
+    ts = torch.from_numpy(w["tau_scen"]).to(dev)
+    et = torch.from_numpy(np.ascontiguousarray(e, np.float32)).to(dev)
+    sc = torch.from_numpy(w["scen"]).to(dev)
+    ws = torch.empty(P.climber_bgf_workspace_bytes(cfg, nb, dg, m), dtype=torch.uint8, device=dev)
+    y = torch.full(et.shape, float("nan"), dtype=torch.float32, device=dev)
+    score = torch.full((m,), float("nan"), dtype=torch.float32, device=dev)
+    P.climber_bgf_score(cfg, atl, wd, wu, wh, ts, float(w["b_head"]), nb, dg, et, sc, m, y, score, ws)
+    # the same without the optional output
+    score2 = torch.empty_like(score)
+    P.climber_bgf_score(cfg, atl, wd, wu, wh, ts, float(w["b_head"]), nb, dg, et, sc, m, None, score2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(score, score2)
+    return y.cpu().numpy(), score.cpu().numpy()
+
+
+def check_bgf(spec, nb, dg, m):
+    import torch
+    import paper_2502_09888_amd as P
+    say(f"[case] bgf {spec.name} d={spec.d_model} F={spec.d_ffn} n_blocks={nb} d_gate={dg} m={m}")
+    w = W.make_bgf(spec, nb, dg, m)
+    cfg = stack_config(spec)
+    y, sc = gpu_bgf(P, torch, cfg, w, w["e"])
+    _, yr, scr = oracle.bgf(oracle_stack_config(spec), w["atl"], w["tau_scen"], w["w_down"], w["w_up"], w["w_head"],
+                            w["b_head"], w["e"], w["scen"])
+    ey, es = max_abs(y, yr), max_abs(sc, scr)
+    say(f"  fused Y max-abs {ey:.3e} (|Y| rms {np.sqrt((yr ** 2).mean()):.3f}), score max-abs {es:.3e} "
+        f"(score std {scr.std():.3f})")
+    assert np.isfinite(y).all() and ey < 2e-2 and es < 2e-2
+
+
+def test_bgf_small_and_odd_counts():
+    spec = W.StackSpec("bgf-small", B=1, L=128, sub_len=0, M=1, n_layers=1, d_model=128, H=2, dh=64, d_ffn=256,
+                       n_scen=8, n_beh=4, seed=51)
+    check_bgf(spec, nb=4, dg=128, m=301)
+    check_bgf(spec, nb=1, dg=128, m=7)
+    check_bgf(spec, nb=3, dg=256, m=64)
+
+
+def test_bgf_config4_width():
+    spec = W.StackSpec("bgf-cfg4", B=1, L=128, sub_len=0, M=1, n_layers=1, d_model=512, H=8, dh=64, d_ffn=2048,
+                       n_scen=8, n_beh=4, seed=52)
+    check_bgf(spec, nb=4, dg=256, m=1024)
+
+
+def test_multi_block_scoring_end_to_end():
+    # Sec. 3.1.2 + 3.1.4: N_b = 2 blocks with weights of their own; block k encodes subsequence k only and
+    # scores every candidate against it; the two block outputs per candidate are fused into a score
+    import torch
+    import paper_2502_09888_amd as P
+    nb, sub, B, M = 2, 128, 3, 40
+    specs = [W.StackSpec(f"block{k}", B=B, L=sub, sub_len=0, M=M, n_layers=2, d_model=128, H=2, dh=64, d_ffn=256,
+                         n_scen=8, n_beh=4, seed=60 + k, hist_lens=(128, 77, 100)) for k in range(nb)]
+    say(f"[case] multi-block: {nb} blocks of {sub} tokens, B={B}, M={M}")
+    ws_ = [W.make_stack(s) for s in specs]
+    # the candidates (embeddings and ids) are the same for every block
+    for w in ws_[1:]:
+        for n in ("x_cand", "cscen", "cbeh", "cand_off"):
+            w[n] = ws_[0][n]
+    e_gpu, e_ref = [], []
+    for spec, w in zip(specs, ws_):
+        g = GpuStack(w)
+        g.encode()
+        e_gpu.append(g.score())
+        cfg = oracle_stack_config(spec)
+        kc, vc, _ = oracle.stack_encode(cfg, w["layers"], w["tau"], w["tok_off"], w["hist_len"],
+                                        np.nan_to_num(w["x_hist"]), w["scen"], w["beh"])
+        e_ref.append(oracle.stack_score(cfg, w["layers"], w["tau"], w["tok_off"], w["hist_len"], kc, vc,
+                                        w["cand_off"], w["x_cand"], w["cscen"], w["cbeh"]))
+    e_gpu, e_ref = np.stack(e_gpu, axis=1), np.stack(e_ref, axis=1)      # [m, n_blocks, d]
+    assert max_abs(e_gpu, e_ref) < 2e-2
+    fw = W.make_bgf(specs[0], nb, 128, e_gpu.shape[0])
+    fw["scen"] = ws_[0]["cscen"]
+    _, sc = gpu_bgf(P, torch, stack_config(specs[0]), fw, e_gpu)
+    _, _, scr = oracle.bgf(oracle_stack_config(specs[0]), fw["atl"], fw["tau_scen"], fw["w_down"], fw["w_up"],
+                           fw["w_head"], fw["b_head"], e_ref, fw["scen"])
+    e = max_abs(sc, scr)
+    say(f"  block outputs max-abs {max_abs(e_gpu, e_ref):.3e}, final scores max-abs {e:.3e} (std {scr.std():.3f})")
+    assert e < 2e-2
