@@ -102,6 +102,39 @@ def bench_stack(args, torch, P, W):
     pre_ms = timed(step_prepacked, args.steps)
     T, M = int(w["tok_off"][-1]), g.m_total
     d, F, NL = spec.d_model, spec.d_ffn, spec.n_layers
+    # training-side packed forward (Sec. 3.2): histories and candidates through one projection launch
+    # per layer, one-layer scratch cache; same result as encode + score
+    one = P.Config(n_layers=1, d_model=d, n_heads=spec.H, d_head=spec.dh, d_ffn=F, n_scen=spec.n_scen,
+                   n_beh=spec.n_beh, sub_len=spec.sub_len, dtype=P.BF16, qk_scale=spec.qk_scale, rms_eps=spec.rms_eps)
+    sbuf = torch.empty(P.climber_kv_cache_bytes(one, g.padded), dtype=torch.uint8, device="cuda:0")
+    scratch = P.climber_kv_cache_create(one, [int(x) for x in w["hist_len"]], g.padded, sbuf)
+    ws_f = torch.empty(P.climber_workspace_bytes(g.cfg, T + M), dtype=torch.uint8, device="cuda:0")
+
+    def forward_packed():
+        P.climber_sumi_forward(g.cfg, g.layers, g.tau, g.x_hist, g.scen, g.beh, g.x_cand, g.cand_off, g.m_total,
+                               g.m_max, g.cscen, g.cbeh, scratch, None, y, ws_f, packed=packed)
+
+    forward_packed()
+    fwd_ms = timed(forward_packed, args.steps)
+    # bit-wise gating fusion (Eq. (4)) + head over 4 block outputs per candidate (random block outputs
+    # of the hidden states' scale: the module's cost, not a model)
+    nb, dg = 4, 256
+    fw = W.make_bgf(spec, nb, dg, M)
+    bfl = {n.lower(): torch.from_numpy(fw["atl"][n]).to("cuda:0").to(torch.bfloat16).contiguous()
+           for n in ("g1", "Wqkv", "Wo", "g2", "W1", "W2")}
+    fd = {n: torch.from_numpy(fw[n]).to("cuda:0").to(torch.bfloat16).contiguous() for n in ("w_down", "w_up")}
+    fe = torch.from_numpy(fw["e"]).to("cuda:0")
+    fh, fts = torch.from_numpy(fw["w_head"]).to("cuda:0"), torch.from_numpy(fw["tau_scen"]).to("cuda:0")
+    ws_b = torch.empty(P.climber_bgf_workspace_bytes(g.cfg, nb, dg, M), dtype=torch.uint8, device="cuda:0")
+    sc_out = torch.empty(M, dtype=torch.float32, device="cuda:0")
+
+    def bgf():
+        P.climber_bgf_score(g.cfg, bfl, fd["w_down"], fd["w_up"], fh, fts, 0.25, nb, dg, fe, g.cscen, M, None,
+                            sc_out, ws_b)
+
+    bgf()
+    bgf_ms = timed(bgf, args.steps)
+    score()   # y as the timed step leaves it
     per_row = 2.0 * (3 * d * d + d * d + 2 * d * F)
     flop_hist = per_row * T * (NL - 1) + 2.0 * T * 3 * d * d     # last layer stops after K/V
     flop_cand = per_row * M * NL
@@ -133,7 +166,9 @@ def bench_stack(args, torch, P, W):
                          "ms_per_step_weights_prepacked": pre_ms,
                          "gemm_tflops_encode": flop_hist / (enc_ms * 1e-3) / 1e12,
                          "gemm_tflops_score": flop_cand / (sc_ms * 1e-3) / 1e12,
-                         "library_matmul_us_history_rows": lib_us},
+                         "library_matmul_us_history_rows": lib_us,
+                         "packed_forward_ms_weights_prepacked": fwd_ms,
+                         "bgf_score_ms": {"n_blocks": nb, "d_gate": dg, "candidates": M, "ms": bgf_ms}},
            "parity_max_abs_vs_oracle": None}
     if not args.no_cpu:
         # the oracle (whole stack: encode + score) on the host cores for one user of the batch; its

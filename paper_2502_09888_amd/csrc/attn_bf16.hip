@@ -207,17 +207,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         }
     };
 
-    // FAST start: q' = bf16(q*c) from the raw rows in st.qf, empty state (the candidate's own
+    // FAST start: the raw query rows stay in st.qf and the row scale in st.c until the first block's
+    // logits have shown which form of the pass the wave takes; empty state (the candidate's own
     // key/value joins later, from the landing buffer).
     auto init_fast = [&](const float (&c)[QB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const bf16x8 qq = st.qf[qb][s];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) st.qf[qb][s][e] = (__bf16)((float)qq[e] * c[qb]);
-            }
+            st.c[qb] = c[qb];
             st.l[qb] = 0.f;
 #pragma unroll
             for (int db = 0; db < 2; ++db)
@@ -316,7 +312,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     // FAST, SUMI: the candidate's own key/value.  Their rows travel through the same landing
     // buffer while the history loop runs (keys first, values once the keys are consumed), so no
     // wave ever waits for them: weight w = exp2(<q', k_own>), then O += w * v_own.
-    float w_own[QB];
+    float w_own[QB], own_scale[QB];  // own_scale: what turns <q, k_own> in st.qf's units into the exponent
     auto own_k = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
@@ -333,7 +329,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) dot += (float)qq[e] * (float)kk[e];
             }
-            w_own[qb] = __builtin_amdgcn_exp2f(dot + xhalf(dot) + (BIAS ? fb[qb] * bias_self[qb] : 0.f));
+            w_own[qb] = __builtin_amdgcn_exp2f((dot + xhalf(dot) + (BIAS ? fb[qb] * bias_self[qb] : 0.f)) * own_scale[qb]);
             st.l[qb] += hf == 0 ? w_own[qb] : 0.f;
         }
     };
@@ -401,11 +397,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             c[qb] = p.scale_log2e / (tau_in_lds ? tau_lds[tau_idx[qb]] : p.tau[tau_idx[qb]]);
         if constexpr (BIAS) {
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) fb[qb] = c[qb] * p.inv_qk_scale;  // log2(e) / tau
+            for (int qb = 0; qb < QB; ++qb) fb[qb] = p.inv_qk_scale;  // bias in the units of the raw <q, k>
         }
         load_q_lds();
         init_fast(c);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) own_scale[qb] = c[qb];
     }
+    bool fold = false;  // the wave runs the pass with the scale folded into a bf16 query
     if (n_tiles > 0) {
         f32x16 S0[QB], S1[QB];
         bf16x8 P[QB][2];
@@ -416,8 +415,52 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         {
             const KFrags k0 = load_k(lds, lane);
             qk(k0, S0, k_lo);
+            // Which form of the FAST pass?  Folding the row scale c = qk_scale*log2(e)/tau into the bf16
+            // query saves a multiplication per logit but rounds q*c to 8 bits, an error of 2^-9 of every
+            // logit: harmless while the exponents stay small.  The first block's exponents s*c tell:
+            // their root mean square estimates the spread of the row's exponents, and with it the size of
+            // the denominator (log2 of it ~ log2(keys) + 0.35 spread^2 for bell-shaped logits).  Below
+            // kPilotSpread for every row of the wave -> fold; otherwise the queries stay exact and every
+            // logit is multiplied by c in fp32.  A wrong guess is caught by the window on the denominators.
+            // (Waves decide on their own: both forms read the same tiles and pass the same barriers.)
+            bool big = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                float ss = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) ss = fmaf(S0[qb][r], S0[qb][r], ss);
+                ss += xhalf(ss);  // the 32 keys of the block
+                big |= !(ss * st.c[qb] * st.c[qb] < kBlockKeys * kPilotSpread * kPilotSpread);
+            }
+            fold = __builtin_amdgcn_ballot_w64(big) == 0;
+            if (fold) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+                    for (int sx = 0; sx < 4; ++sx) {
+                        const bf16x8 qq = st.qf[qb][sx];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) st.qf[qb][sx][e] = (__bf16)((float)qq[e] * st.c[qb]);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) S0[qb][r] *= st.c[qb];
+                    own_scale[qb] = 1.f;
+                    if constexpr (BIAS) fb[qb] = st.c[qb] * p.inv_qk_scale;  // log2(e) / tau
+                }
+            }
             causal(S0, k_lo);
         }
+        auto run = [&](auto fold_tag) __attribute__((always_inline)) {
+        constexpr bool FOLD = decltype(fold_tag)::value;
+        // p = exp2(t): t straight from the MFMA (FOLD), or s * c in fp32
+        auto soft = [&](const f32x16 (&S)[QB]) __attribute__((always_inline)) {
+            if constexpr (FOLD) {
+                softmax_fast(st, S, P);
+            } else {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) st.l[qb] += exp_pack<true>(S[qb], st.c[qb], 0.f, P[qb]);
+            }
+        };
         // One step = every tile but the last: 64 unmasked keys.  EV numbers the tile that becomes
         // readable in the middle of the step when something rides along with its refill or is
         // due afterwards (the own rows of a candidate tile); 0 = plain step.  The steps with
@@ -436,7 +479,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 __builtin_amdgcn_sched_barrier(0);
                 qk(k1, S1, k_lo + t * kTileKeys + kBlockKeys);
                 causal(S1, k_lo + t * kTileKeys + kBlockKeys);
-                softmax_fast(st, S0, P);
+                soft(S0);
                 pv_block(st, v0, P);
             }
             // tile t+1 becomes readable (kStages == 3: no later tile is in flight, the wait
@@ -456,7 +499,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 __builtin_amdgcn_sched_barrier(0);
                 qk(k0, S0, k_lo + (t + 1) * kTileKeys);
                 causal(S0, k_lo + (t + 1) * kTileKeys);
-                softmax_fast(st, S1, P);
+                soft(S1);
                 pv_block(st, v1, P);
             }
         };
@@ -493,16 +536,21 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             if (tile_lo + kBlockKeys > k_hi) mask_block(S0, hf, tile_lo, k_hi);
             {
                 const VFrags v0 = load_v(cur, lane);
-                softmax_fast(st, S0, P);
+                soft(S0);
                 pv_block(st, v0, P);
             }
             if (two) {
                 if (tile_lo + kTileKeys > k_hi) mask_block(S1, hf, tile_lo + kBlockKeys, k_hi);
                 const VFrags v1 = load_v(cur + kBlockBytes, lane);
-                softmax_fast(st, S1, P);
+                soft(S1);
                 pv_block(st, v1, P);
             }
         }
+        };
+        if (__builtin_expect(fold, 1))
+            run(std::true_type{});
+        else
+            run(std::false_type{});
     }
 
     // lane % 32 again, opaquely: otherwise the compiler carries the old copy across the loop (in
@@ -531,7 +579,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         lt[qb] = st.l[qb] + xhalf(st.l[qb]);
-        bad |= !(lt[qb] > kDenomLo && lt[qb] < kDenomHi);
+        bad |= fold ? !(lt[qb] > kDenomLo && lt[qb] < kDenomHi) : !(lt[qb] > kDenomLoExact && lt[qb] < kDenomHiExact);
     }
     // Workgroup-wide OR of `bad` through the (idle) landing buffer: one flag per wave in its own
     // slice, one barrier; the barrier also orders the reuse of the LDS ring below.

@@ -23,6 +23,14 @@ constexpr float kSafeSlack = 8.0f;           // SAFE: exp2-domain slack before t
 // by the SAFE pass, which scales in fp32.
 constexpr float kDenomHi = 1048576.f;        // 2^20
 constexpr float kDenomLo = 1.f / 1048576.f;  // 2^-20
+// The exact-scale form of the FAST pass (queries unrounded, p = exp2(s * c) with c in fp32) has no
+// error that grows with the logits; its window only keeps the exponentials inside the fp32 / bf16
+// exponent range.
+constexpr float kDenomHiExact = 1.0e30f;
+constexpr float kDenomLoExact = 1.0e-30f;
+// largest root mean square of the first block's exponents s * c (log2 units) for which a wave
+// folds c into its bf16 queries
+constexpr float kPilotSpread = 4.25f;
 constexpr float kSafeNoRef = -1.0e30f;       // SAFE: "no reference yet", below any finite logit
 
 // Per-wave softmax state for QB blocks of 32 queries.
