@@ -93,7 +93,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     constexpr int WQ = 32 * QB;  // query rows per wave
     constexpr int TQ = NW * WQ;  // query rows per workgroup
     constexpr int NPRE = kTileBytes / 16 / NT;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kStages * kTileBytes + TQ * 128];
+    // BIAS: this head's rows of the two bias tables live behind the landing buffer when they fit
+    // (lookups per logit: LDS gathers instead of gathers from global memory)
+    constexpr int kBiasLds = BIAS ? kBiasLdsFloats : 0;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kStages * kTileBytes + TQ * 128 + kBiasLds * 4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar
     int l32 = lane & 31;
@@ -184,6 +187,20 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     // per query row of the lane: position, time stamp, rows of the two bias tables, logit scale
     int b_pos[QB], b_ts[QB], b_prow[QB], b_trow[QB];
     float fb[QB], bias_self[QB];
+    // LDS copy of the head's table rows: [n_tau][n_pos] then [n_tau][n_time]
+    const float *bias_lds = (const float *)(lds + kStages * kTileBytes + TQ * 128);
+    const int n_groups = p.n_scen * p.n_beh;
+    const bool bias_in_lds = BIAS && n_groups * (p.bias.n_pos + p.bias.n_time) <= kBiasLds;
+    if constexpr (BIAS) {
+        if (bias_in_lds) {  // visible to the workgroup after the barrier that follows the first tile's wait
+            float *dst = (float *)(lds + kStages * kTileBytes + TQ * 128);
+            const int np_ = p.bias.n_pos, nt_ = p.bias.n_time;
+            for (int i = tid; i < n_groups * np_; i += NT)
+                dst[i] = p.bias.pos_table[((i / np_) * p.bias_H + h) * np_ + i % np_];
+            for (int i = tid; i < n_groups * nt_; i += NT)
+                dst[n_groups * np_ + i] = p.bias.time_table[((i / nt_) * p.bias_H + h) * nt_ + i % nt_];
+        }
+    }
     auto qk = [&](const KFrags &kf, f32x16 (&S)[QB], int blk_lo) __attribute__((always_inline)) {
         if constexpr (BIAS) {
             const int half = (p.bias.n_pos - 1) >> 1;
@@ -196,10 +213,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-                        S[qb][4 * g4 + e] =
-                            fb[qb] * (p.bias.pos_table[b_prow[qb] + bias_bucket_pos(b_pos[qb], kpe[e], half)] +
-                                      p.bias.time_table[b_trow[qb] + bias_bucket_time(b_ts[qb], kte[e], p.bias.n_time)]);
+                    for (int qb = 0; qb < QB; ++qb) {
+                        const int ip = b_prow[qb] + bias_bucket_pos(b_pos[qb], kpe[e], half);
+                        const int it = b_trow[qb] + bias_bucket_time(b_ts[qb], kte[e], p.bias.n_time);
+                        S[qb][4 * g4 + e] = fb[qb] * (bias_in_lds ? bias_lds[ip] + bias_lds[it]
+                                                                  : p.bias.pos_table[ip] + p.bias.time_table[it]);
+                    }
             }
             qk_block_acc(st, kf, S);
         } else {
@@ -292,12 +311,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     // conflict-free.  A wave only ever touches its own slice of that buffer.
     uint8_t *rows_lds = lds + kStages * kTileBytes + wave * (WQ * 128);
     auto issue_rows = [&](const __bf16 *base, int64_t ld) __attribute__((always_inline)) {
+        // wave-uniform base (the tile's first row) in scalar registers + a 32-bit offset per lane (at most
+        // TQ - 1 rows): half the address registers of 64-bit lane addresses
+        const uint8_t *sb = uniform_ptr((const uint8_t *)(base + row0 * ld + h * kDHead));
 #pragma unroll
         for (int i = 0; i < WQ / 8; ++i) {
             const int pos = i * 64 + lane, r = pos >> 3, c = (pos & 7) ^ (r & 7);
-            const int64_t row = row0 + min(wave * WQ + r, nq - 1);
-            __builtin_amdgcn_global_load_lds((glb_u8 *)(base + row * ld + h * kDHead + c * 8),
-                                             (lds_u8 *)rows_lds + i * 1024, 16, 0, 0);
+            const uint32_t off = ((uint32_t)min(wave * WQ + r, nq - 1) * (uint32_t)ld + (uint32_t)c * 8u) * 2u;
+            __builtin_amdgcn_global_load_lds((glb_u8 *)sb + off, (lds_u8 *)rows_lds + i * 1024, 16, 0, 0);
         }
     };
     auto load_q_lds = [&]() __attribute__((always_inline)) {
@@ -312,7 +333,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     // FAST, SUMI: the candidate's own key/value.  Their rows travel through the same landing
     // buffer while the history loop runs (keys first, values once the keys are consumed), so no
     // wave ever waits for them: weight w = exp2(<q', k_own>), then O += w * v_own.
-    float w_own[QB], own_scale[QB];  // own_scale: what turns <q, k_own> in st.qf's units into the exponent
+    float w_own[QB];
+    bool fold = false;  // the wave runs the pass with the scale folded into a bf16 query (decided below)
     auto own_k = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
@@ -329,7 +351,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) dot += (float)qq[e] * (float)kk[e];
             }
-            w_own[qb] = __builtin_amdgcn_exp2f((dot + xhalf(dot) + (BIAS ? fb[qb] * bias_self[qb] : 0.f)) * own_scale[qb]);
+            w_own[qb] = __builtin_amdgcn_exp2f((dot + xhalf(dot) + (BIAS ? fb[qb] * bias_self[qb] : 0.f)) * (fold ? 1.f : st.c[qb]));
             st.l[qb] += hf == 0 ? w_own[qb] : 0.f;
         }
     };
@@ -375,10 +397,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             const int64_t row = row0 + min(wave * WQ + qb * 32 + l32, nq - 1);
             b_pos[qb] = p.bias.q_pos[row];
             b_ts[qb] = p.bias.q_ts[row];
-            b_prow[qb] = (tau_idx[qb] * p.bias_H + h) * p.bias.n_pos;
-            b_trow[qb] = (tau_idx[qb] * p.bias_H + h) * p.bias.n_time;
+            const int grow = (tau_idx[qb] * p.bias_H + h);
             // a candidate's own key: zero distance in position and time
-            bias_self[qb] = p.bias.pos_table[b_prow[qb] + ((p.bias.n_pos - 1) >> 1)] + p.bias.time_table[b_trow[qb]];
+            bias_self[qb] = p.bias.pos_table[grow * p.bias.n_pos + ((p.bias.n_pos - 1) >> 1)] +
+                            p.bias.time_table[grow * p.bias.n_time];
+            // rows of the lane's (scenario, behaviour) pair: in the LDS copy, or in the tables themselves
+            b_prow[qb] = bias_in_lds ? tau_idx[qb] * p.bias.n_pos : grow * p.bias.n_pos;
+            b_trow[qb] = bias_in_lds ? n_groups * p.bias.n_pos + tau_idx[qb] * p.bias.n_time : grow * p.bias.n_time;
         }
     }
     // tile 0 and the query rows of this wave have landed (only tile 1 may still be in flight);
@@ -401,10 +426,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         }
         load_q_lds();
         init_fast(c);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) own_scale[qb] = c[qb];
     }
-    bool fold = false;  // the wave runs the pass with the scale folded into a bf16 query
     if (n_tiles > 0) {
         f32x16 S0[QB], S1[QB];
         bf16x8 P[QB][2];
@@ -443,8 +465,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                         for (int e = 0; e < 8; ++e) st.qf[qb][sx][e] = (__bf16)((float)qq[e] * st.c[qb]);
                     }
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) S0[qb][r] *= st.c[qb];
-                    own_scale[qb] = 1.f;
+                    for (int r = 0; r < 16; ++r) S0[qb][r] *= st.c[qb];  // the first block's logits, formed already
                     if constexpr (BIAS) fb[qb] = st.c[qb] * p.inv_qk_scale;  // log2(e) / tau
                 }
             }

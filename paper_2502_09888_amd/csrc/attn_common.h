@@ -31,7 +31,8 @@ constexpr float kDenomLoExact = 1.0e-30f;
 // largest root mean square of the first block's exponents s * c (log2 units) for which a wave
 // folds c into its bf16 queries
 constexpr float kPilotSpread = 4.25f;
-constexpr float kSafeNoRef = -1.0e30f;       // SAFE: "no reference yet", below any finite logit
+constexpr float kSafeNoRef = -1.0e30f;
+constexpr int kBiasLdsFloats = 4096;         // LDS floats for one head's rows of the bias tables       // SAFE: "no reference yet", below any finite logit
 
 // Per-wave softmax state for QB blocks of 32 queries.
 template <int QB>
@@ -45,6 +46,15 @@ struct QState {
 
 struct KFrags { bf16x8 a[4]; };  // K A-operands of a 32-key block (4 k-steps of 16 dims)
 struct VFrags { bf16x8 a[2][2]; };  // V^T A-operands [16-key group][32-dim block]
+
+// A pointer the caller knows to be wave-uniform, as a value in scalar registers.
+static __device__ __forceinline__ const uint8_t *uniform_ptr(const uint8_t *p)
+{
+    const uint64_t a = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    return (const uint8_t *)(((uint64_t)hi << 32) | lo);
+}
 
 static __device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32, 64); }
 
