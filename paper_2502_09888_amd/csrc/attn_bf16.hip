@@ -16,21 +16,25 @@
 //     rows arrive the same way in a landing buffer behind the ring, one slice per wave.
 //   - FAST pass.  Softmax does not depend on the reference subtracted from the logits as long as
 //     numerator and denominator share it, and fp32 / bf16 carry 8 exponent bits, so for logits of
-//     ordinary size NO reference is needed at all: with the per-row temperature folded into the
-//     query, q' = bf16(q * qk_scale*log2(e)/tau_row), a logit is t = <q',k> straight out of the
-//     MFMA, p = exp2(t), and it costs one v_exp_f32, half a v_cvt_pk_bf16_f32 and one v_add_f32
-//     (denominator) -- no row maximum, no subtraction, no rescale of O.  The loop is software
-//     pipelined over 32-key blocks: the S^T MFMAs of block i+1 are issued before the exponentials
-//     of block i, so matrix and vector pipes overlap inside one wave.
-//   - SAFE pass.  Rounding q' to bf16 costs every logit a relative 2^-9, i.e. an error that grows
-//     with the logit.  If any row's denominator leaves [kDenomLo, kDenomHi] (or is not finite)
-//     the workgroup redoes its work with the classical online softmax: unscaled q, fp32 scale
+//     ordinary size NO reference is needed at all: p = exp2(t) with t the logit in log2 units, one
+//     v_exp_f32, half a v_cvt_pk_bf16_f32 and one v_add_f32 (denominator) per logit -- no row
+//     maximum, no subtraction, no rescale of O.  Two forms, chosen per wave from the first block's
+//     logits: "folded", q' = bf16(q * c) with c = qk_scale*log2(e)/tau_row, so that t = <q',k>
+//     comes straight out of the MFMA (rounding q*c costs every logit a relative 2^-9: kept only
+//     while a row's denominator stays in [kDenomLo, kDenomHi]); and "exact scale", q as given and
+//     t = <q,k> * c in fp32 (one more multiplication per logit; the denominator only has to stay
+//     inside the exponent range, [kDenomLoExact, kDenomHiExact]).  The loop is software pipelined
+//     over 32-key blocks: the S^T MFMAs of block i+1 are issued before the exponentials of block
+//     i, so matrix and vector pipes overlap inside one wave.
+//   - SAFE pass.  If any row's denominator leaves its window (or is not finite) the workgroup
+//     redoes its work with the classical online softmax: unscaled q, fp32 scale
 //     p = exp2(s*c - m*c), running row maximum (moved when exceeded by 2^8, O and l rescaled).
-//     This covers logits of any size; it is never taken for unit-scale logits.  The decision is
-//     per workgroup, so a row's rounding depends on whether a neighbour of its tile has large
-//     logits: results are bitwise independent of the other rows only within one mode.
-//   - SUMI: the candidate's own key/value initialise the running state, which is the "+ itself"
-//     term of the mask.
+//     This covers logits of any size.  The choice of form is per wave and the redo per workgroup,
+//     so a row's rounding depends on whether a neighbour of its tile has large logits: results
+//     are bitwise independent of the other rows only within one form.
+//   - SUMI: the candidate's own key / value join the softmax as one more member (FAST: between
+//     two tiles, from the landing buffer; SAFE: as the initial state): the "+ itself" term of the
+//     mask.
 #include "attn_common.h"
 
 #include <type_traits>

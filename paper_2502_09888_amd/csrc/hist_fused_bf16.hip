@@ -20,9 +20,10 @@
 // Slots past a user's valid length hold zeros in the cache and are masked in the softmax whatever
 // the source rows contain (the raw rows are zeroed in LDS after landing); padded query rows
 // produce zeros.
-// The softmax is the FAST / SAFE scheme of attn_bf16.hip (no reference subtraction unless a
-// denominator leaves [1e-12, 1e12]); here the SAFE redo is per wave, since waves share only
-// read-only data.
+// The softmax is the folded FAST form of attn_bf16.hip (row scale folded into a bf16 query, no
+// reference subtraction) with its window [kDenomLo, kDenomHi] on the denominators; a wave whose
+// rows leave the window redoes its subsequence with the SAFE online softmax -- per wave, since
+// waves share only read-only data.
 #include "attn_common.h"
 
 #include <algorithm>
