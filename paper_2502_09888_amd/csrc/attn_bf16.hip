@@ -189,7 +189,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
     auto issue_tile = [&](int t) __attribute__((always_inline)) { issue_tile_at(t, (t % kStages) * kTileBytes); };
     QState<QB> st;
     // per query row of the lane: position, time stamp, rows of the two bias tables, logit scale
-    int b_pos[QB], b_ts[QB], b_prow[QB], b_trow[QB];
+    int b_pos[QB];
+    uint32_t b_ts[QB];               // time stamp, sign bit flipped (bias_time_key)
+    const float *b_prow[QB], *b_trow[QB];  // the row's slices of the two tables (LDS copy or global)
     float fb[QB], bias_self[QB];
     // LDS copy of the head's table rows: [n_tau][n_pos] then [n_tau][n_time]
     const float *bias_lds = (const float *)(lds + kStages * kTileBytes + TQ * 128);
@@ -213,15 +215,15 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             for (int g4 = 0; g4 < 4; ++g4) {
                 const int4 kp = *(const int4 *)(p.bias.key_pos + kr + 8 * g4);
                 const int4 kt = *(const int4 *)(p.bias.key_ts + kr + 8 * g4);
-                const int kpe[4] = {kp.x, kp.y, kp.z, kp.w}, kte[4] = {kt.x, kt.y, kt.z, kt.w};
+                const int kpe[4] = {kp.x, kp.y, kp.z, kp.w};
+                const uint32_t kte[4] = {bias_time_key(kt.x), bias_time_key(kt.y), bias_time_key(kt.z), bias_time_key(kt.w)};
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) {
-                        const int ip = b_prow[qb] + bias_bucket_pos(b_pos[qb], kpe[e], half);
-                        const int it = b_trow[qb] + bias_bucket_time(b_ts[qb], kte[e], p.bias.n_time);
-                        S[qb][4 * g4 + e] = fb[qb] * (bias_in_lds ? bias_lds[ip] + bias_lds[it]
-                                                                  : p.bias.pos_table[ip] + p.bias.time_table[it]);
+                        const int ip = bias_bucket_pos(b_pos[qb], kpe[e], half);
+                        const int it = bias_bucket_time_u(b_ts[qb], kte[e], p.bias.n_time);
+                        S[qb][4 * g4 + e] = fb[qb] * (b_prow[qb][ip] + b_trow[qb][it]);
                     }
             }
             qk_block_acc(st, kf, S);
@@ -400,14 +402,15 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
         if constexpr (BIAS) {
             const int64_t row = row0 + min(wave * WQ + qb * 32 + l32, nq - 1);
             b_pos[qb] = p.bias.q_pos[row];
-            b_ts[qb] = p.bias.q_ts[row];
+            b_ts[qb] = bias_time_key(p.bias.q_ts[row]);
             const int grow = (tau_idx[qb] * p.bias_H + h);
             // a candidate's own key: zero distance in position and time
             bias_self[qb] = p.bias.pos_table[grow * p.bias.n_pos + ((p.bias.n_pos - 1) >> 1)] +
                             p.bias.time_table[grow * p.bias.n_time];
             // rows of the lane's (scenario, behaviour) pair: in the LDS copy, or in the tables themselves
-            b_prow[qb] = bias_in_lds ? tau_idx[qb] * p.bias.n_pos : grow * p.bias.n_pos;
-            b_trow[qb] = bias_in_lds ? n_groups * p.bias.n_pos + tau_idx[qb] * p.bias.n_time : grow * p.bias.n_time;
+            b_prow[qb] = bias_in_lds ? bias_lds + tau_idx[qb] * p.bias.n_pos : p.bias.pos_table + grow * p.bias.n_pos;
+            b_trow[qb] = bias_in_lds ? bias_lds + n_groups * p.bias.n_pos + tau_idx[qb] * p.bias.n_time
+                                     : p.bias.time_table + grow * p.bias.n_time;
         }
     }
     // tile 0 and the query rows of this wave have landed (only tile 1 may still be in flight);

@@ -22,18 +22,27 @@ struct BiasArgs {
 
 static __device__ __forceinline__ int bias_bucket_pos(int pos_q, int pos_k, int half)
 {
-    // |difference| as an unsigned value: exact for any two int32
-    const uint32_t a = pos_q >= pos_k ? (uint32_t)pos_q - (uint32_t)pos_k : (uint32_t)pos_k - (uint32_t)pos_q;
-    const int m = (int)(a < (uint32_t)half ? a : (uint32_t)half);
-    return pos_q >= pos_k ? half + m : half - m;
+    // the saturating difference clips exactly like the true one (half < 2^30): exact for any two int32
+    const int d = __builtin_elementwise_sub_sat(pos_q, pos_k);
+    return min(max(d, -half), half) + half;
+}
+
+// Flipping the sign bit maps int32 onto uint32 in order, so |ts_q - ts_k| = |u(ts_q) - u(ts_k)| as an
+// unsigned value, exact for any two int32.  Callers with many keys per query flip each side once.
+static __device__ __forceinline__ uint32_t bias_time_key(int ts) { return (uint32_t)ts ^ 0x80000000u; }
+
+static __device__ __forceinline__ int bias_bucket_time_u(uint32_t uq, uint32_t uk, int n_time)
+{
+    uint32_t a;
+    asm("v_sad_u32 %0, %1, %2, 0" : "=v"(a) : "v"(uq), "v"(uk));  // |uq - uk|
+    // floor(log2(max(a, 1))) = floor(log2(a | 1)): position of the highest set bit
+    const int b = 31 - __builtin_clz(a | 1u);
+    return min(b, n_time - 1);
 }
 
 static __device__ __forceinline__ int bias_bucket_time(int ts_q, int ts_k, int n_time)
 {
-    uint32_t a = ts_q >= ts_k ? (uint32_t)ts_q - (uint32_t)ts_k : (uint32_t)ts_k - (uint32_t)ts_q;
-    a = a < 1u ? 1u : a;
-    const int b = 31 - __builtin_clz(a);
-    return b < n_time - 1 ? b : n_time - 1;
+    return bias_bucket_time_u(bias_time_key(ts_q), bias_time_key(ts_k), n_time);
 }
 
 }  // namespace climber

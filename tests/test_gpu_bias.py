@@ -113,6 +113,22 @@ def test_bf16_bias_single_bucket_tables_and_edges():
     assert e < 2e-2
 
 
+def test_bias_buckets_at_the_ends_of_the_int32_range():
+    # positions and time stamps at and near the ends of int32: differences that overflow 32-bit
+    # subtraction, every one of the 32 possible log2 buckets of |ts_i - ts_j| has a table entry of its own
+    ends = np.array([-2**31, -2**31 + 1, -2**30, -3, -1, 0, 1, 2, 2**30, 2**31 - 2, 2**31 - 1], dtype=np.int64)
+    for dtype, tol_key in (("f32", "f32"), ("bf16", "bf16")):
+        base = W.CONFIG1 if dtype == "f32" else W.CONFIG2
+        spec = (W.shrink(base, name="f32-bias-ends", B=2, L=192, sub_len=64, M=33, seed=88) if dtype == "f32" else
+                W.shrink(base, name="bf16-bias-ends", B=2, L=256, sub_len=128, M=70, H=2, seed=89))
+        w = W.add_bias_inputs(W.make_attention(spec), n_pos=7, n_time=34, table_std=1.0)
+        rng = np.random.default_rng(5)
+        for n in ("hist_pos", "hist_ts", "cand_pos", "cand_ts"):
+            pick = rng.random(w[n].shape) < 0.5
+            w[n][pick] = rng.choice(ends, size=int(pick.sum())).astype(np.int32)
+        check_bias(w)
+
+
 def test_bf16_bias_large_logits_take_the_running_maximum_pass():
     spec = W.shrink(W.CONFIG2, name="bf16-bias-biglogits", B=2, L=256, sub_len=128, M=100, H=2, qk_scale=12.0,
                     seed=85)
