@@ -464,16 +464,35 @@ int climber_sumi_forward(const climber_config *cfg, const climber_weights *weigh
         const bool last = l + 1 == cfg->n_layers;
         const PackedLayer pw = packed_layer(cfg, ws, l);
         const float *tau_l = tau + l * tl;
-        // one fused projection over both kinds of rows
-        TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xb, d, pw.wqkv, (int)R, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, nin, no_out, 0,
-                         s)));
+        const size_t crow = (size_t)T * 3 * d * 2;  // the candidates' part of the projection output
         const uint8_t *q = ws.qkv, *k = q + (size_t)d * 2, *v = q + (size_t)2 * d * 2;
-        const size_t crow = (size_t)T * 3 * d * 2;  // first candidate row of the projection output
         // the history's outputs of the last layer feed nothing unless the caller wants them
         const bool hist_out = !last || y_hist;
-        // history rows: keys / values into layer 0 of the scratch cache, attention inside the subsequences
-        TRY(attn_history_strided(cfg, tau_l, q, k, v, 3 * d, scen, beh, scratch_cache, 0, hist_out ? ws.o : nullptr, d,
-                                 s));
+        QkvToCache qc;
+        if (T > 0 && cache_direct_target(cfg, scratch_cache, 0, &qc)) {
+            // history rows: the projection's epilogue writes keys and values into layer 0 of the scratch
+            // cache as operand fragments and the queries as rows of d (none of them when nothing follows);
+            // the candidates' rows get a projection launch of their own
+            if (hist_out) {
+                TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xb, d, pw.wqkv, (int)T, 3 * d, d, ws.qkv, d, nullptr, 0, nin, no_out,
+                                 0, s, &qc)));
+                TRY(attn_history_cached(cfg, tau_l, ws.qkv, d, scen, beh, scratch_cache, 0, ws.o, d, s));
+            } else {
+                qc.which0 = 1;
+                TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xb, d, pw.wqkv + (size_t)d * d * 2, (int)T, 2 * d, d, ws.qkv, d,
+                                 nullptr, 0, nin, no_out, 0, s, &qc)));
+            }
+            const RowNormIn nin_c{ws.ss + (size_t)T * np, np, 1.f / (float)d, cfg->rms_eps};
+            TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xb + (size_t)T * d * 2, d, pw.wqkv, m_total, 3 * d, d, ws.qkv + crow,
+                             3 * d, nullptr, 0, nin_c, no_out, 0, s)));
+        } else {
+            // one fused projection over both kinds of rows; keys / values of the history rows into layer 0
+            // of the scratch cache through rows, attention inside the subsequences
+            TRY(rt(gemm_bf16(EPI_STORE_BF16, ws.xb, d, pw.wqkv, (int)R, 3 * d, d, ws.qkv, 3 * d, nullptr, 0, nin, no_out,
+                             0, s)));
+            TRY(attn_history_strided(cfg, tau_l, q, k, v, 3 * d, scen, beh, scratch_cache, 0, hist_out ? ws.o : nullptr,
+                                     d, s));
+        }
         // candidate rows: the whole history of this layer plus themselves
         TRY(attn_sumi_strided(cfg, tau_l, scratch_cache, 0, q + crow, k + crow, v + crow, 3 * d, cand_off, m_total,
                               m_max, cand_scen, cand_beh, ws.o + (size_t)T * d * 2, d, s));

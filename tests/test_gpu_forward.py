@@ -60,10 +60,15 @@ def test_packed_forward_small_ragged_both_masks():
                        nan_padding=True)
     run_forward(spec, users=(0, 1, 2, 3))
     run_forward(spec, users=(0, 1, 3), want_hist=False)
+    # keys / values through rows (one projection launch over both kinds of rows) instead of straight
+    # into the scratch cache
+    run_forward(spec, users=(0, 1, 2, 3), flags=4)
+    run_forward(spec, users=(0, 1, 3), want_hist=False, flags=4)
     spec = W.StackSpec("fwd-causal", B=2, L=256, sub_len=128, M=50, n_layers=3, d_model=128, H=2, dh=64, d_ffn=256,
                        n_scen=8, n_beh=4, seed=92, hist_lens=(256, 200), causal=True, w_std=0.04)
     run_forward(spec, users=(0, 1))
     run_forward(spec, users=(0, 1), flags=2)
+    run_forward(spec, users=(0, 1), flags=4)
 
 
 def test_packed_forward_equals_encode_then_score_within_rounding():
@@ -75,6 +80,10 @@ def test_packed_forward_equals_encode_then_score_within_rounding():
     e = max_abs(yc[:g.m_total], ys)
     say(f"  packed forward vs encode + score: max-abs {e:.3e}")
     assert e < 2e-2
+    # with the keys / values going straight into the cache on both sides the two are the same kernels
+    # on the same rows: equal bits
+    if not (g.cfg.flags & 4):
+        assert np.array_equal(yc[:g.m_total], ys)
 
 
 def test_packed_forward_config4_full_size_sampled_users():
