@@ -297,8 +297,9 @@ int climber_sumi_score(const climber_config *cfg, const climber_weights *weights
  * that section (history rows: own subsequence; a candidate: its user's whole history and itself,
  * never another candidate) and nothing is cached across calls -- the forward pass behind the
  * paper's training-throughput figure.  Same result as climber_history_encode followed by
- * climber_sumi_score; one projection launch per layer covers both kinds of rows, and the history
- * keys / values of the layer being computed live in layer 0 of `scratch_cache` (a cache handle
+ * climber_sumi_score (bitwise for y_cand under the default flags); the output projection and
+ * feed-forward launches of a layer cover both kinds of rows, and the history keys / values of the
+ * layer being computed live in layer 0 of `scratch_cache` (a cache handle
  * created for this batch's histories with any number of layers; its layer 0 is overwritten).
  * y_hist: dev fp32 [rows][d_model] or NULL (then the last layer skips the history rows' attention
  * and feed-forward); y_cand: dev fp32 [m_total][d_model].  workspace must hold
