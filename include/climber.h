@@ -329,8 +329,8 @@ int climber_sumi_forward(const climber_config *cfg, const climber_weights *weigh
  * climber_sumi_score or climber_sumi_forward: its y_cand rows are E(S_k).
  * e: dev fp32 [m_total][n_blocks][d_model]; cand_scen: dev int32 [m_total]; y: dev fp32 like e, or
  * NULL; score: dev fp32 [m_total].  CLIMBER_BF16, d_head = 64, 1 <= n_blocks <= 16, d_gate a
- * multiple of 128 and <= n_blocks * d_model.  workspace: climber_bgf_workspace_bytes(), 256-byte
- * aligned.  Errors: CLIMBER_ERR_NULL, _SHAPE, _UNSUPPORTED, _ALIGN, _RANGE, _BUFSIZE, _RUNTIME. */
+ * multiple of 128 and <= n_blocks * d_model.  e, y, w_down, w_up, w_head: 16-byte aligned.
+ * workspace: climber_bgf_workspace_bytes(), 256-byte aligned.  Errors: CLIMBER_ERR_NULL, _SHAPE, _UNSUPPORTED, _ALIGN, _RANGE, _BUFSIZE, _RUNTIME. */
 typedef struct climber_bgf_weights {
     climber_layer_weights atl; /* fusion layer, bf16, shapes of a stack layer */
     const void *w_down;        /* dev bf16 [n_blocks * d_model][d_gate] */

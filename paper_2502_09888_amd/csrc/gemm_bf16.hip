@@ -18,6 +18,7 @@
 //   2 x 2 (macro tile 128 x 128): for problems too small to fill the chip with larger tiles.
 // Workgroups that share A rows are launched onto the same XCD (see the kernel).
 #include "gemm.h"
+#include "lanes.h"
 
 #include <algorithm>
 #include <cstdlib>
@@ -84,19 +85,6 @@ __device__ __forceinline__ float gelu_erf(float x)
     const float e = __builtin_amdgcn_exp2f((x * x) * -0.72134752044448170f);
     const float h = (poly * t) * e;
     return fmaf(-a, h, fmaxf(x, 0.f));
-}
-
-// sum over the 16 lanes of a DPP row, in every lane of the row (cross-lane adds on the VALU)
-__device__ __forceinline__ float row_sum16(float x)
-{
-    auto dpp = [](float v, auto ctrl) {
-        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xf, 0xf, false));
-    };
-    x += dpp(x, std::integral_constant<int, 0xB1>{});   // quad_perm [1,0,3,2]
-    x += dpp(x, std::integral_constant<int, 0x4E>{});   // quad_perm [2,3,0,1]
-    x += dpp(x, std::integral_constant<int, 0x141>{});  // row_half_mirror
-    x += dpp(x, std::integral_constant<int, 0x140>{});  // row_mirror
-    return x;
 }
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), unrolled at compile time

@@ -391,7 +391,7 @@ int climber_bgf_score(const climber_config *cfg, const climber_bgf_weights *w, c
     const int64_t R = (int64_t)m_total * nb;
     if (R * (int64_t)std::max(F, 3 * d) >= (int64_t)1 << 31) return CLIMBER_ERR_RANGE;
     if ((uintptr_t)workspace % 256 != 0 || (uintptr_t)e % 16 != 0 || (uintptr_t)y % 16 != 0 ||
-        (uintptr_t)w->w_down % 16 != 0 || (uintptr_t)w->w_up % 16 != 0)
+        (uintptr_t)w->w_down % 16 != 0 || (uintptr_t)w->w_up % 16 != 0 || (uintptr_t)w->w_head % 16 != 0)
         return CLIMBER_ERR_ALIGN;
     climber_config one = *cfg;
     one.n_layers = 1;

@@ -54,6 +54,9 @@ def test_bgf_small_and_odd_counts():
     check_bgf(spec, nb=4, dg=128, m=301)
     check_bgf(spec, nb=1, dg=128, m=7)
     check_bgf(spec, nb=3, dg=256, m=64)
+    # many blocks: the attention kernel is instantiated per block count up to 16
+    check_bgf(spec, nb=16, dg=128, m=45)
+    check_bgf(spec, nb=7, dg=128, m=130)
 
 
 def test_bgf_config4_width():
