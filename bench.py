@@ -440,14 +440,18 @@ def main():
     single_ms = sumi_ms if nch == 1 else other_ms
     seq4_ms = other_ms if nch == 1 else sumi_ms * 4
     # configuration 3 scores its 512 candidates per user "in 4 chunks of 128": both forms side by side
-    # (scoring launches only; frac = algorithmic flop of all 512 candidates / time / bf16 MFMA peak)
-    out["variants"] = {
-        "one_call_of_512": {"score_ms": single_ms, "candidates_per_s": cands / (single_ms * 1e-3),
-                            "mfma_frac": flop_all / (single_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
-        "four_calls_of_128_one_stream": {"score_ms": seq4_ms, "candidates_per_s": cands / (seq4_ms * 1e-3),
-                                         "mfma_frac": flop_all / (seq4_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
-        "four_calls_of_128_four_streams": {"score_ms": streams_ms, "candidates_per_s": cands / (streams_ms * 1e-3),
-                                           "mfma_frac": flop_all / (streams_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}}
+    # (scoring launches only; mfma_frac = algorithmic flop of all 512 candidates / time / bf16 MFMA peak; the
+    # four-call forms read the cache once per call, which makes them HBM-bound: hbm_frac is their roofline)
+    # algorithmic bytes: a call reads the K/V cache of the batch once and moves its candidates' q, k, v, o rows
+    kv_bytes = 2.0 * B * H * L * dh * 2
+    row_bytes = 4.0 * B * M * H * dh * 2
+    def variant(ms, n_calls):
+        byts = n_calls * kv_bytes + row_bytes
+        return {"score_ms": ms, "candidates_per_s": cands / (ms * 1e-3),
+                "mfma_frac": flop_all / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                "algorithmic_GBps": byts / (ms * 1e-3) / 1e9, "hbm_frac": byts / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    out["variants"] = {"one_call_of_512": variant(single_ms, 1), "four_calls_of_128_one_stream": variant(seq4_ms, 4),
+                       "four_calls_of_128_four_streams": variant(streams_ms, 4)}
     out["breakdown"]["relative_attention_bias"] = {
         "sumi_with_bias_ms": sumi_bias_ms, "sumi_without_ms": score_ms if nch == 1 else other_ms,
         "history_with_bias_ms": hist_bias_ms, "history_without_ms": encode_ms,
