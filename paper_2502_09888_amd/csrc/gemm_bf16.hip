@@ -21,6 +21,7 @@
 #include "lanes.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 #include <utility>
@@ -444,10 +445,20 @@ hipError_t launch(const __bf16 *a, int64_t lda, const __bf16 *w, int M, int N, i
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr size_t lds_bytes = (size_t)kStages * (BM + BN) * BK * 2;
-    static const hipError_t attr = hipFuncSetAttribute(
-        (const void *)gemm_bf16_kernel<EPI, WM, WN, kStages>, hipFuncAttributeMaxDynamicSharedMemorySize,
-        (int)lds_bytes);
-    if (attr != hipSuccess) return attr;
+    // the kernel's dynamic LDS exceeds the default limit: raised once per device (the attribute belongs
+    // to the function as loaded on the current device)
+    constexpr int kMaxDevices = 64;
+    static std::atomic<bool> raised[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!raised[dev].load(std::memory_order_acquire)) {
+        e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<EPI, WM, WN, kStages>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        raised[dev].store(true, std::memory_order_release);
+    }
     const dim3 grid((N / BN) * ((M + BM - 1) / BM)), block(256);
     hipLaunchKernelGGL((gemm_bf16_kernel<EPI, WM, WN, kStages>), grid, block, lds_bytes, s, a, lda, w, M, N, K,
                        C, ldc, resid, ldr, nin, nout, tiled, qc);
