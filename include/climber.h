@@ -43,8 +43,7 @@
  *  - CLIMBER_BF16: bf16 storage, bf16 MFMA products with fp32 accumulation, fp32
  *    softmax statistics, probabilities rounded to bf16 before the P V product;
  *    requires d_head == 64, padded history lengths that are multiples of 64 and
- *    sub_len == 0 or a multiple of 128.  Under CLIMBER_HIST_CAUSAL the history pass runs as cache
- *    write + tiled attention (the one-kernel pass for sub_len 128 / 256 is not causal).
+ *    sub_len == 0 or a multiple of 128.
  */
 #ifndef CLIMBER_H
 #define CLIMBER_H
@@ -71,8 +70,8 @@ extern "C" {
 
 #define CLIMBER_HIST_CAUSAL 1 /* flags bit 0: history token i only sees j <= i of its subsequence */
 /* Path selection, results equal to within rounding.  The bf16 history pass has two routes where
- * sub_len is 128 or 256 and the causal flag is off: one kernel that stores the cache blocks and
- * attends (default), or cache writer + tiled attention (the route of every other sub_len). */
+ * sub_len is 128 or 256: one kernel that stores the cache blocks and attends (default), or cache
+ * writer + tiled attention (the route of every other sub_len). */
 #define CLIMBER_HIST_TWO_KERNEL 2 /* flags bit 1: always take the cache writer + tiled attention route */
 /* The stack's fused QKV projection writes history keys / values into the cache from its epilogue
  * (default), or stores them as rows that the history pass then copies into the cache. */

@@ -59,7 +59,10 @@ struct Item {
 // blockIdx.x, blockIdx.x + gridDim.x, ...  While a subsequence is attended to, the rows of the
 // next one are already on their way into the second set of buffers, so HBM stays busy through
 // the compute phases and no wave ever waits for rows.
-template <int SUB>
+// CAUSAL (token i sees the keys j <= i of its subsequence): wave w's 32 queries stop after key block w,
+// whose logits are masked per lane; the wave still reads and stores what it is responsible for (block w
+// of the cache image), which its own blocks 0 .. w cover.
+template <int SUB, bool CAUSAL = false>
 __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HParams p)
 {
     static_assert(SUB == 128 || SUB == 256, "fragments of the whole subsequence stay in LDS");
@@ -309,6 +312,7 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
         // ---- 5. attention of the subsequence's own queries, 32 per wave ----------------------
         QState<1> st;
         const int n_blk = (g.n_valid + kBlockKeys - 1) / kBlockKeys;
+        const int n_att = CAUSAL ? min(n_blk, wv + 1) : n_blk;  // key blocks this wave's queries attend to
         auto run = [&](auto safe_tag) __attribute__((always_inline)) {
             constexpr bool SAFE = decltype(safe_tag)::value;
             f32x16 S0[1], S1[1];
@@ -324,16 +328,16 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             // and this block's exponentials (vector unit) then run while the V^T reads are on their way.
             // The K registers are requested again as soon as the MFMAs that read them have been issued.
             KRaw kr;
-            if (n_blk > 0) {
+            if (n_att > 0) {
                 read_k(kraw, 0, kr);
                 const KFrags k0 = done_k(kr, std::integral_constant<int, 0>{});
                 qk_block(st, k0, S0);
                 if (!SAFE) store_k(0, k0);
-                if (n_blk > 1) read_k(kraw, 1, kr);
+                if (n_att > 1) read_k(kraw, 1, kr);
             }
             auto block = [&](int blk, f32x16 (&Sc)[1], f32x16 (&Sn)[1]) __attribute__((always_inline)) {
                 VRaw vr;
-                const bool next = blk + 1 < n_blk, next2 = blk + 2 < n_blk;
+                const bool next = blk + 1 < n_att, next2 = blk + 2 < n_att;
                 read_v(vraw, blk, vr);
                 if (next) {
                     const KFrags kn = done_k(kr, std::integral_constant<int, 8>{});
@@ -342,6 +346,10 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
                     if (next2) read_k(kraw, blk + 2, kr);
                 }
                 if (32 * (blk + 1) > g.n_valid) mask_block(Sc, hf, 32 * blk, g.n_valid);
+                if (CAUSAL && blk == wv) {  // the diagonal block: the lane's query is row 32 wv + l32
+                    const int lim[1] = {32 * wv + l32 + 1};
+                    mask_causal(Sc, hf, 32 * blk, lim);
+                }
                 if (SAFE) softmax_safe(st, Sc, P); else softmax_fast(st, Sc, P);
                 const VFrags vf = done_v(vr, next2);
                 pv_block(st, vf, P);
@@ -360,8 +368,8 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             constexpr int kHalf = NB == 8 ? NB / 4 : NB / 2;
 #pragma unroll 1
             for (int b2 = 0; b2 < kHalf; ++b2) {
-                if (2 * b2 < n_blk) block(2 * b2, S0, S1);
-                if (2 * b2 + 1 < n_blk) block(2 * b2 + 1, S1, S0);
+                if (2 * b2 < n_att) block(2 * b2, S0, S1);
+                if (2 * b2 + 1 < n_att) block(2 * b2 + 1, S1, S0);
             }
             if (NB == 8) {
                 if (!SAFE) {
@@ -370,8 +378,8 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
                 }
 #pragma unroll 1
                 for (int b2 = kHalf; b2 < NB / 2; ++b2) {
-                    if (2 * b2 < n_blk) block(2 * b2, S0, S1);
-                    if (2 * b2 + 1 < n_blk) block(2 * b2 + 1, S1, S0);
+                    if (2 * b2 < n_att) block(2 * b2, S0, S1);
+                    if (2 * b2 + 1 < n_att) block(2 * b2 + 1, S1, S0);
                 }
             }
         };
@@ -435,7 +443,7 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
 
 }  // namespace
 
-bool hist_fused_supported(int sub_len, int causal) { return !causal && (sub_len == 128 || sub_len == 256); }
+bool hist_fused_supported(int sub_len, int causal) { (void)causal; return sub_len == 128 || sub_len == 256; }
 
 hipError_t launch_hist_fused_bf16(const AttnArgs &a, hipStream_t s)
 {
@@ -473,10 +481,12 @@ hipError_t launch_hist_fused_bf16(const AttnArgs &a, hipStream_t s)
     }();
     if (a.sub_len == 256) {  // 160 KiB of LDS: one 8-wave workgroup per CU
         const unsigned grid = (unsigned)std::min<int64_t>(items, n_cu);
-        hipLaunchKernelGGL(hist_fused_kernel<256>, dim3(grid), dim3(512), 0, s, p);
+        if (a.causal) hipLaunchKernelGGL((hist_fused_kernel<256, true>), dim3(grid), dim3(512), 0, s, p);
+        else hipLaunchKernelGGL((hist_fused_kernel<256, false>), dim3(grid), dim3(512), 0, s, p);
     } else {                 // 80 KiB: two 4-wave workgroups per CU
         const unsigned grid = (unsigned)std::min<int64_t>(items, 2 * n_cu);
-        hipLaunchKernelGGL(hist_fused_kernel<128>, dim3(grid), dim3(256), 0, s, p);
+        if (a.causal) hipLaunchKernelGGL((hist_fused_kernel<128, true>), dim3(grid), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((hist_fused_kernel<128, false>), dim3(grid), dim3(256), 0, s, p);
     }
     return hipGetLastError();
 }

@@ -63,16 +63,24 @@ def test_bf16_ragged_lengths_nan_padding():
 
 
 def test_bf16_causal_history():
-    # history token i sees j <= i of its subsequence.  Subsequences of 128 and 256 (the query tile of
-    # 256 rows holds two resp. one of them; under the flag they take the tiled kernel, not the
-    # one-kernel pass), one undivided sequence spanning several query tiles, ragged lengths with
-    # NaN padding; the candidate pass on the cache that the causal history call wrote.
+    # history token i sees j <= i of its subsequence.  Subsequences of 128 and 256 (the one-kernel pass:
+    # wave w stops after key block w; and, under the two-kernel flag, the tiled kernel, whose query
+    # tile of 256 rows holds two resp. one subsequence), one undivided sequence spanning several query
+    # tiles, ragged lengths with NaN padding, large logits (the running-maximum pass of both
+    # kernels); the candidate pass on the cache that the causal history call wrote.
     for name, kw in (("bf16-causal-sub128", dict(B=3, L=384, sub_len=128, M=40, H=2, seed=41)),
                      ("bf16-causal-sub256", dict(B=2, L=512, sub_len=256, M=40, H=2, seed=42)),
-                     ("bf16-causal-whole", dict(B=2, L=640, sub_len=0, M=33, H=2, seed=43))):
-        check_all(W.make_attention(W.shrink(W.CONFIG2, name=name, **kw)), causal=True)
+                     ("bf16-causal-whole", dict(B=2, L=640, sub_len=0, M=33, H=2, seed=43)),
+                     ("bf16-causal-biglogits", dict(B=2, L=512, sub_len=256, M=40, H=2, qk_scale=12.0, seed=45))):
+        w = W.make_attention(W.shrink(W.CONFIG2, name=name, **kw))
+        check_all(w, causal=True)
+        check_all(w, causal=True, flags=TWO_KERNEL)
     spec = W.shrink(W.CONFIG5, name="bf16-causal-ragged", B=5, L=700, L_min=1, sub_len=256, M=30,
                     M_min=1, H=2, seed=44)
+    check_all(W.make_attention(spec), causal=True)
+    check_all(W.make_attention(spec), causal=True, flags=TWO_KERNEL)
+    spec = W.shrink(W.CONFIG5, name="bf16-causal-ragged128", B=4, L=500, L_min=1, sub_len=128, M=20,
+                    M_min=1, H=2, seed=46)
     check_all(W.make_attention(spec), causal=True)
 
 
