@@ -205,6 +205,9 @@ def main():
     ap.add_argument("--event-every", type=int, default=4,
                     help="bracket the scoring launch with HIP events on every n-th timed step")
     ap.add_argument("--sets", type=int, default=3, help="independent buffer sets the timed steps rotate over")
+    ap.add_argument("--shape", default=None, metavar="B,L,M",
+                    help="attention workload only: another uniform shape instead of configuration 3's 64,1024,512 "
+                         "(exploration; the line is then labelled as not the metric's configuration)")
     ap.add_argument("--workload", choices=["attention", "stack"], default="attention",
                     help="attention = configuration 3 (the headline metric); stack = configuration 4, "
                          "the full 4-layer block stack (extra line, same JSON shape)")
@@ -227,6 +230,14 @@ def main():
         return bench_stack(args, torch, P, W)
     dev = "cuda:0"
     spec = W.CONFIG3
+    if args.shape:
+        try:
+            sb, sl, sm = (int(x) for x in args.shape.split(","))
+        except ValueError:
+            sys.exit("bench.py: --shape takes B,L,M")
+        if sb < 1 or sl < spec.sub_len or sl % spec.sub_len or sm < 4 or sm % 4:
+            sys.exit(f"bench.py: --shape needs B >= 1, L a multiple of {spec.sub_len}, M a multiple of 4")
+        spec = W.shrink(spec, name=f"shape-{sb}-{sl}-{sm}", B=sb, L=sl, M=sm)
     w = W.make_attention(spec)
     B, L, M, H, dh = spec.B, spec.L, spec.M, spec.H, spec.dh
     d = H * dh
@@ -403,19 +414,21 @@ def main():
     got = torch.stack([ch["o"].view(B, Mc, d) for ch in chunks], dim=1).reshape(B, M, d).float().cpu().numpy()
 
     out = {
-        "metric": "candidates scored/sec/GPU at L=1024,M=512; % bf16 MFMA peak",
+        "metric": "candidates scored/sec/GPU at L=1024,M=512; % bf16 MFMA peak" if not args.shape else
+                  "candidates scored/sec/GPU at B,L,M = %s (exploration, not the metric's configuration)" % args.shape,
         "value": value, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "prewarm_ms": args.prewarm_ms, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "launch_events_every_n_steps": max(1, args.event_every),
-        "config": {"workload": "config3: SUMI attention with KV-cache reuse, bf16; M=512 scored in %d "
-                               "call(s) of %d candidates/user" % (nch, Mc), "B": B, "L": L,
+        "config": {"workload": ("config3" if not args.shape else "NOT the metric's configuration (--shape)") +
+                               ": SUMI attention with KV-cache reuse, bf16; M=%d scored in %d "
+                               "call(s) of %d candidates/user" % (M, nch, Mc), "B": B, "L": L,
                    "sub_len": spec.sub_len, "M": M, "chunks": nch, "heads": H, "d_head": dh,
                    "step": "kv-cache write + block-diagonal history attention + %d SUMI scoring "
                            "call(s) of %d candidates/user" % (nch, Mc)},
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel<SUMI=true>, %d candidates/user per launch" % Mc, "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": measured_traffic(), "launch_ms": sumi_ms, "flop_per_launch": flop_launch,
+                     "traffic": None if args.shape else measured_traffic(), "launch_ms": sumi_ms, "flop_per_launch": flop_launch,
                      "algorithmic_bytes_per_launch": kv_bytes + qkvo_bytes,
                      "algorithmic_GBps": (kv_bytes + qkvo_bytes) / (sumi_ms * 1e-3) / 1e9,
                      "hbm_peak_GBps": PEAK_HBM_GBS,
@@ -450,8 +463,8 @@ def main():
         return {"score_ms": ms, "candidates_per_s": cands / (ms * 1e-3),
                 "mfma_frac": flop_all / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                 "algorithmic_GBps": byts / (ms * 1e-3) / 1e9, "hbm_frac": byts / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
-    out["variants"] = {"one_call_of_512": variant(single_ms, 1), "four_calls_of_128_one_stream": variant(seq4_ms, 4),
-                       "four_calls_of_128_four_streams": variant(streams_ms, 4)}
+    out["variants"] = {f"one_call_of_{M}": variant(single_ms, 1), f"four_calls_of_{M // 4}_one_stream": variant(seq4_ms, 4),
+                       f"four_calls_of_{M // 4}_four_streams": variant(streams_ms, 4)}
     out["breakdown"]["relative_attention_bias"] = {
         "sumi_with_bias_ms": sumi_bias_ms, "sumi_without_ms": score_ms if nch == 1 else other_ms,
         "history_with_bias_ms": hist_bias_ms, "history_without_ms": encode_ms,
