@@ -61,7 +61,9 @@ struct Item {
 // the compute phases and no wave ever waits for rows.
 // CAUSAL (token i sees the keys j <= i of its subsequence): wave w's 32 queries stop after key block w,
 // whose logits are masked per lane; the wave still reads and stores what it is responsible for (block w
-// of the cache image), which its own blocks 0 .. w cover.
+// of the cache image), which its own blocks 0 .. w cover.  Rows that see few keys have sharply peaked
+// softmaxes, where the 2^-9 that folding the scale into a bf16 query costs every logit shows in the
+// output: the causal variant keeps the query as given and multiplies the logits by the scale in fp32.
 template <int SUB, bool CAUSAL = false>
 __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HParams p)
 {
@@ -350,7 +352,9 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
                     const int lim[1] = {32 * wv + l32 + 1};
                     mask_causal(Sc, hf, 32 * blk, lim);
                 }
-                if (SAFE) softmax_safe(st, Sc, P); else softmax_fast(st, Sc, P);
+                if (SAFE) softmax_safe(st, Sc, P);
+                else if (CAUSAL) st.l[0] += exp_pack<true>(Sc[0], st.c[0], 0.f, P[0]);  // exact scale: p = exp2(s * c)
+                else softmax_fast(st, Sc, P);
                 const VFrags vf = done_v(vr, next2);
                 pv_block(st, vf, P);
                 if (!SAFE) store_v(blk, vf);
@@ -388,9 +392,9 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             bf16x8 q_raw[4];
             read_q(q_raw);
 #pragma unroll
-            for (int s = 0; s < 4; ++s)  // FAST: q' = bf16(q * c)
+            for (int s = 0; s < 4; ++s)  // FAST: q' = bf16(q * c); CAUSAL: q as given, the scale in fp32
 #pragma unroll
-                for (int e = 0; e < 8; ++e) st.qf[0][s][e] = (__bf16)((float)q_raw[s][e] * st.c[0]);
+                for (int e = 0; e < 8; ++e) st.qf[0][s][e] = CAUSAL ? q_raw[s][e] : (__bf16)((float)q_raw[s][e] * st.c[0]);
         }
         run(std::false_type{});
         for (int kb = n_blk; kb < nb_pad; ++kb) {  // blocks of padding only: zeros
@@ -399,7 +403,7 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             else { put(kb, wv, zero); put(kb, wv + 4, zero); }
         }
         float lt = st.l[0] + xhalf(st.l[0]);
-        const bool bad = g.n_valid > 0 && !(lt > kDenomLo && lt < kDenomHi);
+        const bool bad = g.n_valid > 0 && !(CAUSAL ? lt > kDenomLoExact && lt < kDenomHiExact : lt > kDenomLo && lt < kDenomHi);
         if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // SAFE (rare): unscaled q, running maximum
             read_q(st.qf[0]);  // the staging slice still holds the wave's query rows
             run(std::true_type{});

@@ -176,6 +176,15 @@ def test_full_size_every_user(spec):
     K, V = decode_bf16_cache(g.buf.cpu().numpy(), spec.B, w["tok_off"], spec.H)
     assert np.array_equal(K[0][ok], w["kh"][ok]) and np.array_equal(V[0][ok], w["vh"][ok])
     assert np.all(K[0][~ok] == 0) and np.all(V[0][~ok] == 0)
+    if spec is W.CONFIG3:
+        # the same full-size launch under the causal flag (persistent one-kernel pass, 2048 subsequences)
+        gc = GpuAttention(w, causal=True)
+        ohc = gc.history()
+        e = max_abs(ohc[ok], oracle_history(w, causal=True)[ok])
+        say(f"  causal history max-abs over all users {e:.3e}")
+        assert e < 2e-2
+        Kc, Vc = decode_bf16_cache(gc.buf.cpu().numpy(), spec.B, w["tok_off"], spec.H)
+        assert np.array_equal(Kc[0][ok], w["kh"][ok]) and np.array_equal(Vc[0][ok], w["vh"][ok])
 
 
 def test_two_kernel_history_path():
