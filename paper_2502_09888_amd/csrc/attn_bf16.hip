@@ -462,8 +462,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 big |= !(ss * st.c[qb] * st.c[qb] < kBlockKeys * kPilotSpread * kPilotSpread);
             }
             // (causal rows see few keys and have sharply peaked softmaxes, where the folded form's error
-            // shows in the output: they always take the exact form)
-            fold = !CAUSAL && __builtin_amdgcn_ballot_w64(big) == 0;
+            // shows in the output: they always take the exact form; so do the bias variants, whose logits
+            // are larger by the bias and whose cost lies elsewhere)
+            fold = !CAUSAL && !BIAS && __builtin_amdgcn_ballot_w64(big) == 0;
             if (fold) {
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {

@@ -135,14 +135,22 @@ def test_bf16_bias_large_logits_take_the_running_maximum_pass():
     check_bias(W.add_bias_inputs(W.make_attention(spec), table_std=20.0))
 
 
-def test_bf16_bias_zero_tables_equal_the_bias_free_kernel_bitwise():
+def test_bf16_bias_zero_tables_reproduce_the_bias_free_result():
+    # zero tables: the bias variant computes the bias-free attention (it keeps the query exact and
+    # scales the logits in fp32 where the plain kernel folds the scale into the query, so the two agree
+    # to rounding, not bit for bit); both against the bias-free oracle
     spec = W.shrink(W.CONFIG2, name="bf16-bias-zero", B=2, L=384, sub_len=128, M=100, H=2, seed=86)
     w = W.add_bias_inputs(W.make_attention(spec))
     w["pos_table"][:] = 0
     w["time_table"][:] = 0
     g = GpuBias(w)
     g.history(want_output=False)
-    assert np.array_equal(g.sumi_bias(), g.sumi())
+    ref = oracle.attn_sumi(w["tok_off"], w["hist_len"], w["cand_off"], w["kh"], w["vh"], w["qc"], w["kc"], w["vc"],
+                           w["cscen"], w["cbeh"], w["tau"], spec.qk_scale)
+    with_zero, plain = g.sumi_bias(), g.sumi()
+    say(f"[case] bias {spec.name}: zero tables vs bias-free kernel {max_abs(with_zero, plain):.3e}, vs bias-free oracle "
+        f"{max_abs(with_zero, ref):.3e} (bias-free kernel: {max_abs(plain, ref):.3e})")
+    assert max_abs(with_zero, ref) < 2e-2 and max_abs(with_zero, plain) < 2e-2
 
 
 def test_bias_at_config2_and_config3_shapes():
