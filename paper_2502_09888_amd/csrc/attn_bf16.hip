@@ -461,10 +461,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 ss += xhalf(ss);  // the 32 keys of the block
                 big |= !(ss * st.c[qb] * st.c[qb] < kBlockKeys * kPilotSpread * kPilotSpread);
             }
-            // (causal rows see few keys and have sharply peaked softmaxes, where the folded form's error
-            // shows in the output: they always take the exact form; so do the bias variants, whose logits
-            // are larger by the bias and whose cost lies elsewhere)
-            fold = !CAUSAL && !BIAS && __builtin_amdgcn_ballot_w64(big) == 0;
+            // Only the candidate pass folds: its rows have the whole history to average over.  History rows
+            // see one subsequence (a few keys only under the causal flag) and can be sharply peaked, where
+            // the folded form's error shows in the output; the bias variants have larger logits and their
+            // cost lies elsewhere.  Those always take the exact form.
+            fold = SUMI && !BIAS && __builtin_amdgcn_ballot_w64(big) == 0;
             if (fold) {
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {

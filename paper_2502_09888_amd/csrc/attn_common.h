@@ -152,10 +152,17 @@ static __device__ __forceinline__ void mask_causal(f32x16 (&S)[QB], int hf, int 
 }
 
 // p = exp2(S*scale - sub) rounded to bf16 in B-operand order (P[g] holds the keys of 16-key
-// group g); returns the sum of the values before rounding (round-to-nearest is unbiased, so the
-// denominator and the bf16 numerators agree to well below the bf16 rounding of a single term).
-// Plain v_add_f32 on purpose: the v_dot2 family issues into the matrix pipe and would take MFMA
-// slots, whereas adds overlap with the MFMAs of the other wave on the SIMD.
+// group g); returns the row's share of the denominator.
+//   AFFINE = false (scale folded into the query, logits of ordinary size): the sum of the values
+//     before rounding.  Round-to-nearest is unbiased, so with many comparable terms the denominator
+//     and the bf16 numerators agree to well below the bf16 rounding of a single term, and the sum
+//     costs one addition per value.
+//     Plain v_add_f32 on purpose: the v_dot2 family issues into the matrix pipe and would take MFMA
+//     slots there, whereas adds overlap with the MFMAs of the other wave on the SIMD.
+//   AFFINE = true (fp32 scale: large logits, causal rows, bias, the history pass that is bound by
+//     memory, the running-maximum pass): the sum of the ROUNDED values.  These rows can be sharply
+//     peaked; a single dominant probability rounded to bf16 in the numerator and not in the
+//     denominator would put its rounding, a relative 2^-9, straight into the output.
 template <bool AFFINE>
 static __device__ __forceinline__ float exp_pack(const f32x16 &S, float scale, float sub, bf16x8 (&P)[2])
 {
@@ -168,7 +175,16 @@ static __device__ __forceinline__ float exp_pack(const f32x16 &S, float scale, f
             const float p1 = __builtin_amdgcn_exp2f(AFFINE ? fmaf(S[8 * g + e + 1], scale, -sub) : S[8 * g + e + 1]);
             P[g][e] = (__bf16)p0;
             P[g][e + 1] = (__bf16)p1;
-            sum += p0 + p1;
+            if constexpr (AFFINE) {
+                // sum += P[e] * 1 + P[e + 1] * 1 on the rounded pair, one instruction (it issues into the
+                // matrix pipe, which these forms leave room in).  Through the builtin, not inline assembly:
+                // the compiler knows the wait states the instruction needs before its result is read.
+                typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+                const bf16x2_t pr = {P[g][e], P[g][e + 1]}, ones = {(__bf16)1.f, (__bf16)1.f};
+                sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
+            } else {
+                sum += p0 + p1;
+            }
         }
     return sum;
 }

@@ -20,10 +20,11 @@
 // Slots past a user's valid length hold zeros in the cache and are masked in the softmax whatever
 // the source rows contain (the raw rows are zeroed in LDS after landing); padded query rows
 // produce zeros.
-// The softmax is the folded FAST form of attn_bf16.hip (row scale folded into a bf16 query, no
-// reference subtraction) with its window [kDenomLo, kDenomHi] on the denominators; a wave whose
-// rows leave the window redoes its subsequence with the SAFE online softmax -- per wave, since
-// waves share only read-only data.
+// The softmax is the exact-scale FAST form of attn_bf16.hip (query as given, logits multiplied by the
+// row scale in fp32, no reference subtraction: this pass is bound by memory, so the multiplication is
+// free and the 2^-9 per logit of the folded form is saved) with the window [kDenomLoExact,
+// kDenomHiExact] on the denominators; a wave whose rows leave the window redoes its subsequence
+// with the SAFE online softmax -- per wave, since waves share only read-only data.
 #include "attn_common.h"
 
 #include <algorithm>
@@ -61,9 +62,7 @@ struct Item {
 // the compute phases and no wave ever waits for rows.
 // CAUSAL (token i sees the keys j <= i of its subsequence): wave w's 32 queries stop after key block w,
 // whose logits are masked per lane; the wave still reads and stores what it is responsible for (block w
-// of the cache image), which its own blocks 0 .. w cover.  Rows that see few keys have sharply peaked
-// softmaxes, where the 2^-9 that folding the scale into a bf16 query costs every logit shows in the
-// output: the causal variant keeps the query as given and multiplies the logits by the scale in fp32.
+// of the cache image), which its own blocks 0 .. w cover.
 template <int SUB, bool CAUSAL = false>
 __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HParams p)
 {
@@ -353,8 +352,7 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
                     mask_causal(Sc, hf, 32 * blk, lim);
                 }
                 if (SAFE) softmax_safe(st, Sc, P);
-                else if (CAUSAL) st.l[0] += exp_pack<true>(Sc[0], st.c[0], 0.f, P[0]);  // exact scale: p = exp2(s * c)
-                else softmax_fast(st, Sc, P);
+                else st.l[0] += exp_pack<true>(Sc[0], st.c[0], 0.f, P[0]);  // exact scale: p = exp2(s * c)
                 const VFrags vf = done_v(vr, next2);
                 pv_block(st, vf, P);
                 if (!SAFE) store_v(blk, vf);
@@ -392,9 +390,9 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             bf16x8 q_raw[4];
             read_q(q_raw);
 #pragma unroll
-            for (int s = 0; s < 4; ++s)  // FAST: q' = bf16(q * c); CAUSAL: q as given, the scale in fp32
+            for (int s = 0; s < 4; ++s)  // q as given: the row scale multiplies the logits in fp32
 #pragma unroll
-                for (int e = 0; e < 8; ++e) st.qf[0][s][e] = CAUSAL ? q_raw[s][e] : (__bf16)((float)q_raw[s][e] * st.c[0]);
+                for (int e = 0; e < 8; ++e) st.qf[0][s][e] = q_raw[s][e];
         }
         run(std::false_type{});
         for (int kb = n_blk; kb < nb_pad; ++kb) {  // blocks of padding only: zeros
@@ -403,7 +401,7 @@ __global__ __launch_bounds__(SUB * 2, 256 / SUB) void hist_fused_kernel(const HP
             else { put(kb, wv, zero); put(kb, wv + 4, zero); }
         }
         float lt = st.l[0] + xhalf(st.l[0]);
-        const bool bad = g.n_valid > 0 && !(CAUSAL ? lt > kDenomLoExact && lt < kDenomHiExact : lt > kDenomLo && lt < kDenomHi);
+        const bool bad = g.n_valid > 0 && !(lt > kDenomLoExact && lt < kDenomHiExact);
         if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // SAFE (rare): unscaled q, running maximum
             read_q(st.qf[0]);  // the staging slice still holds the wave's query rows
             run(std::true_type{});
