@@ -23,7 +23,10 @@
 //     comes straight out of the MFMA (rounding q*c costs every logit a relative 2^-9: kept only
 //     while a row's denominator stays in [kDenomLo, kDenomHi]); and "exact scale", q as given and
 //     t = <q,k> * c in fp32 (one more multiplication per logit; the denominator only has to stay
-//     inside the exponent range, [kDenomLoExact, kDenomHiExact]).  The loop is software pipelined
+//     inside the exponent range, [kDenomLoExact, kDenomHiExact]; the denominator is summed from the
+//     probabilities as rounded to bf16, so that a one-hot row does not carry the rounding of its
+//     dominant term into the output).  Only the candidate pass folds; history rows and the bias
+//     variants always take the exact form.  The loop is software pipelined
 //     over 32-key blocks: the S^T MFMAs of block i+1 are issued before the exponentials of block
 //     i, so matrix and vector pipes overlap inside one wave.
 //   - SAFE pass.  If any row's denominator leaves its window (or is not finite) the workgroup
