@@ -35,6 +35,8 @@
  *    of which the first hist_len[b] are valid.  Padded rows are never read as
  *    keys/values (they may hold anything, NaN included) and produce zeros as
  *    query rows.  Candidates are packed with device offsets cand_off[B+1].
+ *  - An array of zero length may be passed as NULL: with m_total == 0 the per-candidate pointers
+ *    (rows, ids, outputs) are not looked at and nothing is launched for the candidates.
  *  - Activations are token-major: q/k/v are [rows][n_heads][d_head], attention
  *    outputs and hidden states are [rows][d_model], d_model = n_heads * d_head.
  *

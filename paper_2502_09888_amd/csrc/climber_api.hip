@@ -409,8 +409,9 @@ static int attn_sumi_call(const climber_config *cfg, const float *tau_layer,
     if (m_total < 0 || m_max < 0 || m_max > m_total) return CLIMBER_ERR_SHAPE;
     if ((int64_t)m_total * cfg->d_model >= (int64_t)1 << 31) return CLIMBER_ERR_RANGE;
     if (m_total > 0 && m_max == 0) return CLIMBER_ERR_SHAPE;
-    if (!tau_layer || !q_c || !k_c || !v_c || !cand_off || !cand_scen || !cand_beh || !o_c)
-        return CLIMBER_ERR_NULL;
+    if (!tau_layer || !cand_off) return CLIMBER_ERR_NULL;
+    if (m_total == 0) return CLIMBER_OK;  // no candidates: the per-candidate arrays are empty, their pointers free
+    if (!q_c || !k_c || !v_c || !cand_scen || !cand_beh || !o_c) return CLIMBER_ERR_NULL;
     if (!aligned(q_c, 16) || !aligned(k_c, 16) || !aligned(v_c, 16) || !aligned(o_c, 16))
         return CLIMBER_ERR_ALIGN;
     return attn_sumi_strided(cfg, tau_layer, cache, layer, q_c, k_c, v_c, cfg->d_model, cand_off,

@@ -202,9 +202,11 @@ int check_score_args(const climber_config *cfg, const climber_weights *weights, 
 {
     TRY(check_stack_config(cfg));
     TRY(check_stack_call(cfg, cache, 0));
-    if (!tau || !x_cand || !cand_scen || !cand_beh || !y_cand) return CLIMBER_ERR_NULL;
+    if (!tau) return CLIMBER_ERR_NULL;
     TRY(check_weights(cfg, weights));
     TRY(check_cand_args(cfg, cand_off, m_total, m_max));
+    if (m_total == 0) return CLIMBER_OK;  // no candidates: the per-candidate arrays are empty, their pointers free
+    if (!x_cand || !cand_scen || !cand_beh || !y_cand) return CLIMBER_ERR_NULL;
     if ((uintptr_t)x_cand % 16 != 0 || (uintptr_t)y_cand % 16 != 0) return CLIMBER_ERR_ALIGN;
     return CLIMBER_OK;
 }
@@ -436,8 +438,9 @@ int climber_sumi_forward(const climber_config *cfg, const climber_weights *weigh
 {
     TRY(check_stack_config(cfg));
     TRY(check_scratch_cache(cfg, scratch_cache));
-    if (!tau || !x_hist || !scen || !beh || !x_cand || !cand_scen || !cand_beh || !y_cand || !workspace)
-        return CLIMBER_ERR_NULL;
+    if (!tau || !x_hist || !scen || !beh || !workspace) return CLIMBER_ERR_NULL;
+    // (no candidates: the per-candidate arrays are empty, their pointers free)
+    if (m_total > 0 && (!x_cand || !cand_scen || !cand_beh || !y_cand)) return CLIMBER_ERR_NULL;
     TRY(check_weights(cfg, weights));
     TRY(check_cand_args(cfg, cand_off, m_total, m_max));
     const int64_t T = cache_rows(scratch_cache), R = T + m_total;

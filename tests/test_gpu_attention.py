@@ -112,6 +112,21 @@ def test_bf16_shape_sweep():
         check_all(W.make_attention(spec), causal=bool(rng.integers(0, 2)))
 
 
+def test_bf16_randomized_shapes_scales_routes():
+    # a larger seeded sweep that also draws the logit scale (unit scale to far beyond: every softmax form
+    # is taken), the history route and candidate counts across the query-tile sizes
+    rng = np.random.Generator(np.random.Philox(20250210))
+    for i in range(80):
+        L = int(rng.integers(1, 1400))
+        M = int(rng.choice([1, 2, 31, 33, 64, 127, 128, 129, 255, 256, 257, 300, 513]))
+        spec = W.shrink(W.CONFIG2, name=f"bf16-rsweep-{i}", B=int(rng.integers(1, 6)), L=L,
+                        L_min=int(rng.integers(0, L + 1)), sub_len=int(rng.choice([0, 128, 256, 384, 512])), M=M,
+                        M_min=int(rng.integers(1, M + 1)), H=int(rng.integers(1, 5)), pad_to=int(rng.choice([64, 128])),
+                        nan_padding=bool(rng.integers(0, 2)), n_scen=int(rng.integers(1, 9)), n_beh=int(rng.integers(1, 5)),
+                        qk_scale=float(rng.choice([0.125, 0.125, 0.125, 0.3, 0.7, 1.5, 6.0])), seed=6000 + i)
+        check_all(W.make_attention(spec), causal=bool(rng.integers(0, 2)), flags=int(rng.choice([0, TWO_KERNEL])))
+
+
 def test_bf16_single_subsequence_and_odd_lengths():
     spec = W.shrink(W.CONFIG2, name="bf16-onesub", B=2, L=333, L_min=77, sub_len=0, M=70, H=1,
                     nan_padding=True, seed=23)
@@ -131,6 +146,11 @@ def test_bf16_empty_history_and_empty_candidate_set():
     g, o = check_all(w)
     lo, hi = w["cand_off"][1], w["cand_off"][2]
     assert max_abs(o[lo:hi], w["vc"][lo:hi].reshape(hi - lo, -1)) == 0.0
+    # no candidates at all: the per-candidate arrays are empty and may be NULL; the call succeeds
+    import torch
+    zero_off = torch.zeros(spec.B + 1, dtype=torch.int32, device="cuda:0")
+    g.P.climber_attn_sumi(g.cfg, g.tau, g.cache, 0, None, None, None, zero_off, 0, 0, None, None, None)
+    torch.cuda.synchronize()
 
 
 def test_bf16_large_logits_do_not_overflow():

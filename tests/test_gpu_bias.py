@@ -166,3 +166,32 @@ def test_bias_at_config2_and_config3_shapes():
         e = max_abs(g.sumi_bias(), oracle_sumi_bias(w))
         say(f"  sumi+bias max-abs over all users {e:.3e}")
         assert e < 2e-2
+
+
+def test_randomized_shapes_scales_masks_with_bias():
+    # seeded sweep: ragged histories and candidate counts, paddings of 64 / 128, any subsequence length the
+    # API admits, 1..4 heads, logit scales from the unit-scale benchmark to far beyond, both masks,
+    # table sizes from one bucket to more buckets than distances
+    rng = np.random.Generator(np.random.Philox(2502098))
+    done = 0
+    for i in range(60):
+        L = int(rng.integers(1, 1400))
+        M = int(rng.choice([1, 2, 31, 33, 64, 127, 128, 129, 255, 256, 257, 300, 513]))
+        spec = W.shrink(W.CONFIG2, name=f"bias-sweep-{i}", B=int(rng.integers(1, 6)), L=L, L_min=int(rng.integers(1, L + 1)),
+                        sub_len=int(rng.choice([0, 128, 256, 384, 512])), M=M, M_min=int(rng.integers(1, M + 1)),
+                        H=int(rng.integers(1, 5)), pad_to=int(rng.choice([64, 128])), nan_padding=bool(rng.integers(0, 2)),
+                        n_scen=int(rng.integers(1, 9)), n_beh=int(rng.integers(1, 5)),
+                        qk_scale=float(rng.choice([0.125, 0.125, 0.3, 0.7, 1.5, 6.0])), seed=7000 + i)
+        w = W.add_bias_inputs(W.make_attention(spec), n_pos=int(rng.choice([1, 5, 33])), n_time=int(rng.choice([1, 7, 34])),
+                              table_std=float(rng.choice([0.3, 1.0])))
+        causal = bool(rng.integers(0, 2))
+        g = GpuBias(w, causal=causal)
+        oh = g.history_bias()
+        ok = valid_rows(w)
+        e1 = max_abs(oh[ok], oracle_hist_bias(w, causal=causal)[ok])
+        e2 = max_abs(g.sumi_bias(), oracle_sumi_bias(w))
+        say(f"[case] {spec.name} B={spec.B} L={spec.L} sub={spec.sub_len} M={spec.M} H={spec.H} qk_scale={spec.qk_scale} "
+            f"causal={causal}: history+bias {e1:.3e}, sumi+bias {e2:.3e}")
+        assert np.isfinite(oh[ok]).all() and np.all(oh[~ok] == 0) and e1 < 2e-2 and e2 < 2e-2
+        done += 1
+    assert done == 60
