@@ -90,3 +90,31 @@ def test_packed_forward_config4_full_size_sampled_users():
     # full size (B=32, L=1024, M=256, 4 layers): 41k rows per projection launch; four users against
     # the oracle's packed definition (one user's 1280 x 1280 mask per layer and head)
     run_forward(W.CONFIG4, users=(0, 9, 22, 31), want_hist=False)
+
+
+def test_randomized_stack_shapes_and_routes():
+    # seeded sweep over small stacks: 1..3 layers, d_model 128 / 256, ragged histories (down to none)
+    # padded to 64 or 128, candidate counts across the query-tile and GEMM-tile sizes (down to none),
+    # both masks, every route (flags 0, 2, 4, 6), NaN padding; encode + score or the packed forward
+    from test_gpu_stack import run
+    rng = np.random.Generator(np.random.Philox(25020988))
+    for i in range(40):
+        B = int(rng.integers(1, 5))
+        d = int(rng.choice([128, 256]))
+        hist = tuple(int(x) for x in rng.integers(0, 420, size=B))
+        if max(hist) == 0:
+            hist = (50,) + hist[1:]
+        cands = tuple(int(x) for x in rng.choice([0, 1, 5, 37, 128, 129, 200, 260], size=B))
+        if sum(cands) == 0:
+            cands = (9,) + cands[1:]
+        spec = W.StackSpec(f"stack-sweep-{i}", B=B, L=0, sub_len=int(rng.choice([0, 128, 256])), M=0,
+                           n_layers=int(rng.integers(1, 4)), d_model=d, H=d // 64, dh=64, d_ffn=int(rng.choice([256, 512])),
+                           n_scen=int(rng.integers(1, 9)), n_beh=int(rng.integers(1, 5)), seed=9000 + i,
+                           pad_to=int(rng.choice([64, 128])), hist_lens=hist, cand_counts=cands,
+                           nan_padding=bool(rng.integers(0, 2)), causal=bool(rng.integers(0, 2)))
+        users = tuple(b for b in range(B) if cands[b] > 0)
+        flags = int(rng.choice([0, 2, 4, 6]))
+        if rng.integers(0, 2):
+            run(spec, users=users, flags=flags)
+        else:
+            run_forward(spec, users=users, want_hist=bool(rng.integers(0, 2)), flags=flags)
