@@ -207,6 +207,17 @@ def test_full_size_every_user(spec):
         assert np.array_equal(Kc[0][ok], w["kh"][ok]) and np.array_equal(Vc[0][ok], w["vh"][ok])
 
 
+def test_bf16_long_histories():
+    # far longer than the benchmark shapes: 9k..16k behaviours in subsequences of 512, and 20k..32k in
+    # one undivided sequence (512 tile steps per workgroup); candidates against the cache only (the
+    # oracle's history attention would take minutes at these lengths)
+    spec = W.shrink(W.CONFIG5, name="long-16k", B=3, L=16384, L_min=9000, sub_len=512, M=600, M_min=200, H=8, seed=77)
+    check_all(W.make_attention(spec), hist=False)
+    spec = W.shrink(W.CONFIG5, name="long-32k-one-subsequence", B=2, L=32768, L_min=20000, sub_len=0, M=300,
+                    M_min=300, H=2, seed=78)
+    check_all(W.make_attention(spec), hist=False)
+
+
 def test_two_kernel_history_path():
     # Subsequences of 128 / 256 tokens take the one-kernel pass (cache blocks + attention) by
     # default; the same cases must also hold on the other route (cache writer, then tiled attention)
