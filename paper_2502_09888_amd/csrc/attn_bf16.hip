@@ -455,7 +455,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
             // kPilotSpread for every row of the wave -> fold; otherwise the queries stay exact and every
             // logit is multiplied by c in fp32.  A wrong guess is caught by the window on the denominators.
             // (Waves decide on their own: both forms read the same tiles and pass the same barriers.)
-            bool big = false;
+            bool big = k_hi - k_lo < kFoldMinKeys;  // (a short history: too few keys to average the folded form's error over)
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 float ss = 0.f;
@@ -464,7 +464,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_kernel(const KParams p)
                 ss += xhalf(ss);  // the 32 keys of the block
                 big |= !(ss * st.c[qb] * st.c[qb] < kBlockKeys * kPilotSpread * kPilotSpread);
             }
-            // Only the candidate pass folds: its rows have the whole history to average over.  History rows
+            // Only the candidate pass folds, and only against a history of some length: its rows then have
+            // many comparable keys to average the per-logit error over.  History rows
             // see one subsequence (a few keys only under the causal flag) and can be sharply peaked, where
             // the folded form's error shows in the output; the bias variants have larger logits and their
             // cost lies elsewhere.  Those always take the exact form.

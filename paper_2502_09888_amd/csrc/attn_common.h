@@ -29,10 +29,13 @@ constexpr float kDenomLo = 1.f / 1048576.f;  // 2^-20
 constexpr float kDenomHiExact = 1.0e30f;
 constexpr float kDenomLoExact = 1.0e-30f;
 // largest root mean square of the first block's exponents s * c (log2 units) for which a wave
-// folds c into its bf16 queries
+// folds c into its bf16 queries (the benchmark's logits have 2.9 at the smallest temperature), and
+// the fewest keys a row must see for it: the folded form's error per logit averages out over
+// many comparable keys, not over a few
 constexpr float kPilotSpread = 4.25f;
-constexpr float kSafeNoRef = -1.0e30f;
-constexpr int kBiasLdsFloats = 4096;         // LDS floats for one head's rows of the bias tables       // SAFE: "no reference yet", below any finite logit
+constexpr int kFoldMinKeys = 256;
+constexpr float kSafeNoRef = -1.0e30f;       // SAFE: "no reference yet", below any finite logit
+constexpr int kBiasLdsFloats = 4096;         // LDS floats for one head's rows of the bias tables
 
 // Per-wave softmax state for QB blocks of 32 queries.
 template <int QB>

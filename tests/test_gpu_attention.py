@@ -207,6 +207,19 @@ def test_full_size_every_user(spec):
         assert np.array_equal(Kc[0][ok], w["kh"][ok]) and np.array_equal(Vc[0][ok], w["vh"][ok])
 
 
+def test_bf16_short_histories_with_moderate_logits():
+    # candidates against a history of a few dozen keys with logits a few times the unit scale: rows are
+    # peaked without being large, the regime where folding the scale into the query (2^-9 per logit, not
+    # averaged over many keys) once exceeded the bar (2.09e-2); such rows now take the exact form
+    spec = W.shrink(W.CONFIG2, name="bf16-short-history", B=2, L=83, L_min=52, sub_len=512, M=129, M_min=21, H=3,
+                    pad_to=64, n_scen=7, n_beh=1, qk_scale=0.3, seed=6230)
+    check_all(W.make_attention(spec), flags=TWO_KERNEL)
+    for L, qk in ((40, 0.5), (130, 0.3), (255, 0.4)):
+        spec = W.shrink(W.CONFIG2, name=f"bf16-short-history-{L}", B=3, L=L, L_min=L // 2, sub_len=0, M=300, M_min=100,
+                        H=2, pad_to=64, qk_scale=qk, seed=6300 + L)
+        check_all(W.make_attention(spec))
+
+
 def test_bf16_long_histories():
     # far longer than the benchmark shapes: 9k..16k behaviours in subsequences of 512, and 20k..32k in
     # one undivided sequence (512 tile steps per workgroup); candidates against the cache only (the
