@@ -96,6 +96,16 @@ def test_compute_calls_reject_missing_cache_and_pointers():
                                     None) == -1
     assert lib.climber_attn_sumi(None, FAKE, None, 0, FAKE, FAKE, FAKE, FAKE, 8, 8, FAKE, FAKE, FAKE,
                                  None) == -1
+    # the stack calls that need a cache handle: none given
+    from paper_2502_09888_amd.climber import _Weights
+    c4 = P.Config(n_layers=4, n_heads=8, d_head=64, d_ffn=2048, n_scen=8, n_beh=4, sub_len=256)
+    w = _Weights(4, None, FAKE)
+    assert lib.climber_sumi_forward(C.byref(c4), C.byref(w), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 8, 8, FAKE, FAKE,
+                                    None, None, FAKE, FAKE, 1 << 40, None) == -1
+    assert lib.climber_sumi_score_static(C.byref(c4), C.byref(w), FAKE, None, FAKE, FAKE, 8, 8, FAKE, FAKE, FAKE,
+                                         None) == -1
+    assert lib.climber_history_encode(C.byref(c4), C.byref(w), FAKE, FAKE, FAKE, FAKE, None, FAKE, 1 << 40,
+                                      None) == -1
 
 
 def test_check_inputs_rejects_bad_arguments():
@@ -141,6 +151,33 @@ def test_packed_weights_arguments():
     # a stack call given a misaligned packed buffer is rejected before anything is launched
     assert lib.climber_sumi_score(C.byref(c4), C.byref(_Weights(4, None, FAKE + 16)), FAKE, None, FAKE, FAKE,
                                   8, 8, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) in (-1, -3)
+
+
+def test_fusion_module_arguments():
+    # bit-wise gating fusion: sizes and pointers are checked on the host before anything is launched
+    lib = P.load_library()
+    from paper_2502_09888_amd.climber import BgfWeights, LayerWeights
+    c = P.Config(n_layers=1, n_heads=8, d_head=64, d_ffn=2048, n_scen=8, n_beh=4, sub_len=0)
+    assert P.climber_bgf_workspace_bytes(c, 4, 256, 1000) > 0
+    assert P.climber_bgf_workspace_bytes(c, 0, 256, 1000) == 0          # no blocks
+    assert P.climber_bgf_workspace_bytes(c, 17, 256, 1000) == 0         # more blocks than the kernel holds
+    assert P.climber_bgf_workspace_bytes(c, 4, 200, 1000) == 0          # d_gate not a multiple of 128
+    assert P.climber_bgf_workspace_bytes(c, 1, 640, 1000) == 0          # d_gate beyond n_blocks * d_model
+    assert P.climber_bgf_workspace_bytes(c, 4, 256, -1) == 0
+    assert P.climber_bgf_workspace_bytes(cfg(dtype=P.F32, d_head=32, sub_len=0), 4, 256, 10) == 0
+    layer = LayerWeights(*([FAKE] * 6))
+    def score(w, e=FAKE, scen=FAKE, m=8, y=FAKE, sc=FAKE, ws=FAKE, nbytes=1 << 40):
+        return lib.climber_bgf_score(C.byref(c), C.byref(w) if w else None, e, scen, m, y, sc, ws, nbytes, None)
+    good = lambda **kw: BgfWeights(**{**dict(atl=layer, w_down=FAKE, w_up=FAKE, w_head=FAKE, tau_scen=FAKE, b_head=0.0,
+                                             n_blocks=4, d_gate=256), **kw})
+    assert score(None) == -1
+    assert score(good(w_head=None)) == -1 and score(good(tau_scen=None)) == -1
+    assert score(good(atl=LayerWeights(*([FAKE] * 5 + [None])))) == -1
+    assert score(good(), e=None) == -1 and score(good(), sc=None) == -1 and score(good(), ws=None) == -1
+    assert score(good(n_blocks=0)) == -2 and score(good(d_gate=200)) == -7
+    assert score(good(), m=-1) == -2
+    assert score(good(), ws=FAKE + 16) == -3 and score(good(w_head=FAKE + 4)) == -3 and score(good(), y=FAKE + 8) == -3
+    assert score(good(), nbytes=1024) == -6
 
 
 def test_binding_has_no_cpu_fallback(monkeypatch, tmp_path):
