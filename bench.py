@@ -34,6 +34,59 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+def shader_clock_while(fn, torch, seconds=1.2):
+    """Median shader clock (MHz, as `rocm-smi --showclocks` reports it, read-only) while `fn` is launched
+    back to back for `seconds`, the clock of the idle device just before, and the number of samples; None
+    where the tool or its output is not there.  Runs outside the timed region."""
+    import json as _json
+    import shutil
+    import subprocess
+    import threading
+    tool = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    if not os.path.exists(tool):
+        return None
+
+    def read():
+        try:
+            out = subprocess.run([tool, "--showclocks", "--json"], capture_output=True, text=True, timeout=10).stdout
+            card = _json.loads(out)
+            card = card[sorted(card.keys())[0]]
+            for k, v in card.items():
+                if k.startswith("sclk clock speed"):
+                    return float(str(v).strip("()").lower().replace("mhz", ""))
+        except Exception:
+            return None
+        return None
+
+    idle = read()
+    if idle is None:
+        return None
+    samples, stop = [], [False]
+
+    def poll():
+        while not stop[0]:
+            v = read()
+            if v is not None:
+                samples.append(v)
+            time.sleep(0.1)
+
+    th = threading.Thread(target=poll)
+    th.start()
+    t_end, i = time.perf_counter() + seconds, 0
+    while time.perf_counter() < t_end:
+        fn()
+        i += 1
+        if i % 32 == 0:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    stop[0] = True
+    th.join()
+    if len(samples) < 3:
+        return None
+    busy = sorted(samples[1:])   # the first sample may straddle the start of the load
+    return {"idle_mhz": idle, "median_mhz": busy[len(busy) // 2], "min_mhz": busy[0], "samples": len(busy)}
+
+
 def measured_traffic():
     """HBM bytes per SUMI launch from the committed rocprofv3 counter summary (FETCH_SIZE +
     WRITE_SIZE, calibrated against the copy kernel), or None when no summary is present."""
@@ -201,6 +254,7 @@ def main():
     ap.add_argument("--chunks", type=int, default=1, help="scoring calls per step (M split evenly)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle cpu_baseline leg")
     ap.add_argument("--no-naive", action="store_true", help="skip the naive re-encode baseline")
+    ap.add_argument("--no-clocks", action="store_true", help="skip the shader-clock samples (rocm-smi, read-only)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--event-every", type=int, default=4,
                     help="bracket the scoring launch with HIP events on every n-th timed step")
@@ -386,6 +440,10 @@ def main():
     streams_ms = timed(score_4_streams, args.steps)
     flop_all = 4.0 * (L + 1) * dh * H * B * M
 
+    # the shader clock while each of the two launches of the step runs back to back (2.4 GHz is what the
+    # datasheet peak assumes; the device lowers it under the scoring kernel's load)
+    clocks = None if args.no_clocks else {"scoring": shader_clock_while(score, torch), "history_pass": shader_clock_while(encode, torch)}
+
     # relative attention bias (Eq. (3)): the same launches with the bias term, for their cost
     wb = W.add_bias_inputs(w)
     bt = {n: torch.from_numpy(wb[n]).to(dev).contiguous() for n in ("hist_pos", "hist_ts", "cand_pos", "cand_ts",
@@ -465,6 +523,7 @@ def main():
                 "algorithmic_GBps": byts / (ms * 1e-3) / 1e9, "hbm_frac": byts / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
     out["variants"] = {f"one_call_of_{M}": variant(single_ms, 1), f"four_calls_of_{M // 4}_one_stream": variant(seq4_ms, 4),
                        f"four_calls_of_{M // 4}_four_streams": variant(streams_ms, 4)}
+    out["roofline"]["shader_clock"] = clocks
     out["breakdown"]["relative_attention_bias"] = {
         "sumi_with_bias_ms": sumi_bias_ms, "sumi_without_ms": score_ms if nch == 1 else other_ms,
         "history_with_bias_ms": hist_bias_ms, "history_without_ms": encode_ms,
