@@ -142,6 +142,7 @@ def bench_stack(args, torch, P, W):
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     enc_ms, sc_ms = timed(g.encode, args.steps), timed(score, args.steps)
+    clocks = None if args.no_clocks else {"encode": shader_clock_while(g.encode, torch), "score": shader_clock_while(score, torch)}
     # the same step with the weights brought into operand order once (climber_pack_weights) instead
     # of inside every call, as a server with fixed weights would run it; reported beside the value
     packed = torch.empty(P.climber_packed_weights_bytes(g.cfg), dtype=torch.uint8, device="cuda:0")
@@ -214,7 +215,7 @@ def bench_stack(args, torch, P, W):
                       "M": spec.M, "layers": NL, "d_model": d, "d_ffn": F},
            "roofline": {"bound": "mfma", "kernel": "whole step (GEMM + attention flop)",
                         "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                        "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None},
+                        "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "shader_clock": clocks},
            "breakdown": {"encode_ms": enc_ms, "score_ms": sc_ms,
                          "ms_per_step_weights_prepacked": pre_ms,
                          "gemm_tflops_encode": flop_hist / (enc_ms * 1e-3) / 1e12,
