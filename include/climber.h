@@ -46,6 +46,12 @@
  *    softmax statistics, probabilities rounded to bf16 before the P V product;
  *    requires d_head == 64, padded history lengths that are multiples of 64 and
  *    sub_len == 0 or a multiple of 128.
+ *    A candidate's result does not depend on which other candidates are scored with it (the
+ *    mask of Sec. 3.2); on this path it is bitwise the same however the candidates are chunked or
+ *    ordered as long as its logits are of ordinary size.  With large logits the kernel picks the
+ *    form of its softmax (scale folded into the query / applied in fp32 / running maximum) per
+ *    wavefront or workgroup from the rows it holds, so a candidate's rounding can then differ
+ *    with its neighbours in the tile; every form is within the path's tolerance.
  */
 #ifndef CLIMBER_H
 #define CLIMBER_H
