@@ -187,3 +187,12 @@ def test_binding_has_no_cpu_fallback(monkeypatch, tmp_path):
     monkeypatch.setattr(mod, "_LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError):
         mod.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU per box: the benchmark says so instead of pretending to scale
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
